@@ -1,0 +1,334 @@
+/*
+ * CPU oracle for decode-step Multi-Matrix Factorization Attention (MFA).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, fp64
+ * statement of what the GPU library must compute.  Only the tests, the smoke
+ * check and the cpu_baseline leg of the benchmark may call it.  It shares no
+ * code, header, table or constant with the HIP path.
+ *
+ * What is computed (paper, Section 2 "Model Card" and its model-card table):
+ *   - 64 query heads of dimension 256 attend over ONE shared key head and ONE
+ *     shared value head of the same dimension (multi-query softmax attention,
+ *     one query token per sequence at decode time);
+ *   - the query comes from a low-rank factorisation: the hidden state is
+ *     down-projected 7168 -> 2048, normalised, and up-projected to 64*256.
+ *   - each GPU serves a batch of independent sequences (Section 7.1, local
+ *     data-parallel attention), so sequences never interact.
+ *   - the cache holds one key row and one value row per token (Section 6:
+ *     512 bytes per token at 8 bits = 256 key + 256 value elements).
+ *
+ * The paper fixes neither the softmax scale, the kind of normalisation, the
+ * fp8 flavour nor the scale granularity; the readings taken here are
+ *   scale: runtime float (1/16 for head dim 256);
+ *   normalisation: RMSNorm, eps added to the mean square inside the root;
+ *   fp8: OCP e4m3fn (bias 7, no infinity, 0x7F/0xFF are NaN, subnormals kept);
+ *   one fp32 dequantisation scale per cached token per tensor.
+ *
+ * Every floating point sum is carried in double.  Nothing is tiled, fused or
+ * reordered: scores, maximum, exponentials, normaliser and weighted sum are
+ * separate passes over the tokens in index order.
+ *
+ * Parity pins (tests/test_oracle_*.py): brute force in numpy, weights sum to
+ * one, context length one returns the value row, permuted page table equals
+ * contiguous cache, zero query returns the mean value row, key-shift and
+ * token-permutation invariance, split/merge identity through the returned
+ * log-sum-exp, torch fp64 scaled_dot_product_attention / rms_norm / matmul,
+ * exhaustive bf16 and e4m3fn code tables against torch's CPU casts.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_API __attribute__((visibility("default")))
+
+enum { ORACLE_KV_BF16 = 0, ORACLE_KV_E4M3 = 1 };
+
+/* ------------------------------------------------------------------ */
+/* Storage formats, decoded field by field.                            */
+/* ------------------------------------------------------------------ */
+
+/* bfloat16: 1 sign, 8 exponent (bias 127), 7 fraction bits. */
+static double decode_bf16(uint16_t bits)
+{
+    int sign = (bits >> 15) & 1;
+    int expo = (bits >> 7) & 0xFF;
+    int frac = bits & 0x7F;
+    double mag;
+    if (expo == 0xFF)
+        mag = frac ? NAN : INFINITY;
+    else if (expo == 0)
+        mag = ldexp((double)frac, -126 - 7);             /* subnormal */
+    else
+        mag = ldexp((double)(128 + frac), expo - 127 - 7);
+    return sign ? -mag : mag;
+}
+
+/* OCP e4m3fn: 1 sign, 4 exponent (bias 7), 3 fraction bits; no infinity;
+ * exponent 15 with fraction 7 is NaN, every other code is finite (max 448). */
+static double decode_e4m3fn(uint8_t bits)
+{
+    int sign = (bits >> 7) & 1;
+    int expo = (bits >> 3) & 0xF;
+    int frac = bits & 0x7;
+    double mag;
+    if (expo == 0xF && frac == 0x7)
+        mag = NAN;
+    else if (expo == 0)
+        mag = ldexp((double)frac, -6 - 3);               /* subnormal */
+    else
+        mag = ldexp((double)(8 + frac), expo - 7 - 3);
+    return sign ? -mag : mag;
+}
+
+/* double -> bfloat16, round to nearest, ties to even, done directly on the
+ * double so that no intermediate float rounding happens. */
+static uint16_t encode_bf16_rne(double x)
+{
+    uint16_t sign = signbit(x) ? 0x8000u : 0;
+    if (isnan(x)) return (uint16_t)(sign | 0x7FC0u);
+    double a = fabs(x);
+    if (isinf(a)) return (uint16_t)(sign | 0x7F80u);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);              /* a = f * 2^e, f in [0.5, 1)  */
+    int expo = e - 1;                /* a = 1.xxx * 2^expo          */
+    if (expo < -126) expo = -126;    /* subnormal range: fixed quantum */
+    /* quantum of the target grid at this exponent is 2^(expo-7) */
+    double scaled = ldexp(a, 7 - expo);          /* exact */
+    double r = nearbyint(scaled);                /* default mode: ties-to-even */
+    /* r in [0, 256]; value = r * 2^(expo-7) */
+    long mant = (long)r;
+    long biased;
+    if (expo == -126 && mant < 128) {
+        biased = 0;                              /* stays subnormal */
+    } else {
+        biased = expo + 127;
+        if (mant == 256) { mant = 128; biased += 1; }
+        mant -= 128;
+    }
+    if (biased >= 255) return (uint16_t)(sign | 0x7F80u);   /* overflow -> inf */
+    return (uint16_t)(sign | (uint16_t)(biased << 7) | (uint16_t)mant);
+}
+
+ORACLE_API double mfa_oracle_decode_bf16(uint16_t bits)   { return decode_bf16(bits); }
+ORACLE_API double mfa_oracle_decode_e4m3fn(uint8_t bits)  { return decode_e4m3fn(bits); }
+ORACLE_API uint16_t mfa_oracle_encode_bf16(double x)      { return encode_bf16_rne(x); }
+
+/* ------------------------------------------------------------------ */
+/* Threads.                                                            */
+/* ------------------------------------------------------------------ */
+static int g_threads = 0;   /* 0 = OpenMP default */
+
+ORACLE_API void mfa_oracle_set_threads(int n) { g_threads = n > 0 ? n : 0; }
+
+ORACLE_API int mfa_oracle_get_threads(void)
+{
+#ifdef _OPENMP
+    return g_threads > 0 ? g_threads : omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ */
+/* One cached row (key or value) of one token, dequantised to double.  */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    const void  *k, *v;            /* cache or pool base                         */
+    const float *k_scale, *v_scale;/* per-token scales (fp8 only)                */
+    int          kv_dtype;
+    int          D;
+    /* contiguous: token j of sequence b is row b*seq_stride_tokens + j          */
+    int64_t      seq_stride_tokens;
+    /* paged: token j of sequence b is row block_table[b][j/page]*page + j%page  */
+    const int32_t *block_table;
+    int32_t      max_blocks_per_seq;
+    int32_t      page_size;
+} kv_view;
+
+static int64_t token_row(const kv_view *kv, int b, int j)
+{
+    if (kv->block_table) {
+        int32_t page = kv->block_table[(int64_t)b * kv->max_blocks_per_seq + j / kv->page_size];
+        return (int64_t)page * kv->page_size + j % kv->page_size;
+    }
+    return (int64_t)b * kv->seq_stride_tokens + j;
+}
+
+static double kv_elem(const kv_view *kv, const void *base, const float *scale, int64_t row, int d)
+{
+    if (kv->kv_dtype == ORACLE_KV_BF16)
+        return decode_bf16(((const uint16_t *)base)[row * kv->D + d]);
+    return (double)scale[row] * decode_e4m3fn(((const uint8_t *)base)[row * kv->D + d]);
+}
+
+/* ------------------------------------------------------------------ */
+/* Softmax attention of one query row over the L cached tokens of its  */
+/* sequence: the textbook definition in three passes.                  */
+/*   s_j = scale * <q, k_j>;  p_j = exp(s_j - max s);  Z = sum p_j;     */
+/*   out_d = sum_j p_j v_{j,d} / Z;  lse = max s + log Z.               */
+/* weights (optional, length L) receives p_j / Z.                      */
+/* ------------------------------------------------------------------ */
+static void attend_one(const uint16_t *q_row, const kv_view *kv, int b, int L, double scale,
+                       float *out_row, double *lse, double *weights)
+{
+    const int D = kv->D;
+    if (L <= 0) {
+        for (int d = 0; d < D; ++d) out_row[d] = 0.0f;
+        if (lse) *lse = -INFINITY;
+        return;
+    }
+    double *s = (double *)malloc(sizeof(double) * (size_t)L);
+    double *qd = (double *)malloc(sizeof(double) * (size_t)D);
+    double *acc = (double *)malloc(sizeof(double) * (size_t)D);
+    for (int d = 0; d < D; ++d) qd[d] = decode_bf16(q_row[d]);
+
+    for (int j = 0; j < L; ++j) {
+        int64_t row = token_row(kv, b, j);
+        double dot = 0.0;
+        for (int d = 0; d < D; ++d) dot += qd[d] * kv_elem(kv, kv->k, kv->k_scale, row, d);
+        s[j] = scale * dot;
+    }
+    double m = s[0];
+    for (int j = 1; j < L; ++j) if (s[j] > m) m = s[j];
+    double Z = 0.0;
+    for (int j = 0; j < L; ++j) { s[j] = exp(s[j] - m); Z += s[j]; }
+
+    for (int d = 0; d < D; ++d) acc[d] = 0.0;
+    for (int j = 0; j < L; ++j) {
+        int64_t row = token_row(kv, b, j);
+        for (int d = 0; d < D; ++d) acc[d] += s[j] * kv_elem(kv, kv->v, kv->v_scale, row, d);
+    }
+    for (int d = 0; d < D; ++d) out_row[d] = (float)(acc[d] / Z);
+    if (lse) *lse = m + log(Z);
+    if (weights) for (int j = 0; j < L; ++j) weights[j] = s[j] / Z;
+    free(s); free(qd); free(acc);
+}
+
+/* Rows to compute: either every (b,h) pair, or the n_rows pairs listed in
+ * row_b/row_h (used to sample full-size workloads).  Output row r goes to
+ * out + r*D (and lse[r]). */
+static int run_rows(const uint16_t *q, const kv_view *kv, const int32_t *seq_lens,
+                    int B, int H, double scale,
+                    int64_t n_rows, const int32_t *row_b, const int32_t *row_h,
+                    float *out, double *lse)
+{
+    const int D = kv->D;
+    int64_t total = row_b ? n_rows : (int64_t)B * H;
+    int nthreads = mfa_oracle_get_threads();
+    (void)nthreads;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int64_t r = 0; r < total; ++r) {
+        int b = row_b ? row_b[r] : (int)(r / H);
+        int h = row_b ? row_h[r] : (int)(r % H);
+        attend_one(q + ((int64_t)b * H + h) * D, kv, b, seq_lens[b], scale,
+                   out + r * D, lse ? lse + r : NULL, NULL);
+    }
+    return 0;
+}
+
+/* Contiguous cache.  q: bf16 [B,H,D]; k,v: [B, seq_stride_tokens, D] in
+ * kv_dtype; k_scale,v_scale: fp32 [B, seq_stride_tokens] (fp8 only);
+ * out: fp32 [rows, D]; lse: double [rows] or NULL. */
+ORACLE_API int mfa_oracle_decode_attn(const uint16_t *q, const void *k, const void *v,
+                                      const float *k_scale, const float *v_scale, int kv_dtype,
+                                      int64_t seq_stride_tokens, const int32_t *seq_lens,
+                                      int B, int H, int D, double scale,
+                                      int64_t n_rows, const int32_t *row_b, const int32_t *row_h,
+                                      float *out, double *lse)
+{
+    if (kv_dtype != ORACLE_KV_BF16 && kv_dtype != ORACLE_KV_E4M3) return 1;
+    if (kv_dtype == ORACLE_KV_E4M3 && (!k_scale || !v_scale)) return 1;
+    kv_view kv = { k, v, k_scale, v_scale, kv_dtype, D, seq_stride_tokens, NULL, 0, 0 };
+    return run_rows(q, &kv, seq_lens, B, H, scale, n_rows, row_b, row_h, out, lse);
+}
+
+/* Paged cache.  k_pool,v_pool: [n_pages, page_size, D]; scale pools fp32
+ * [n_pages, page_size]; block_table: int32 [B, max_blocks_per_seq]. */
+ORACLE_API int mfa_oracle_decode_attn_paged(const uint16_t *q, const void *k_pool, const void *v_pool,
+                                            const float *k_scale_pool, const float *v_scale_pool,
+                                            int kv_dtype, int32_t page_size,
+                                            const int32_t *block_table, int32_t max_blocks_per_seq,
+                                            const int32_t *seq_lens, int B, int H, int D, double scale,
+                                            int64_t n_rows, const int32_t *row_b, const int32_t *row_h,
+                                            float *out, double *lse)
+{
+    if (kv_dtype != ORACLE_KV_BF16 && kv_dtype != ORACLE_KV_E4M3) return 1;
+    if (kv_dtype == ORACLE_KV_E4M3 && (!k_scale_pool || !v_scale_pool)) return 1;
+    if (!block_table || page_size <= 0) return 1;
+    kv_view kv = { k_pool, v_pool, k_scale_pool, v_scale_pool, kv_dtype, D, 0,
+                   block_table, max_blocks_per_seq, page_size };
+    return run_rows(q, &kv, seq_lens, B, H, scale, n_rows, row_b, row_h, out, lse);
+}
+
+/* Attention weights p_j / Z of one (b,h) row over a contiguous bf16/fp8 cache
+ * (for the rows-sum-to-one pin). weights: double [seq_lens[b]]. */
+ORACLE_API int mfa_oracle_attn_weights(const uint16_t *q, const void *k, const void *v,
+                                       const float *k_scale, const float *v_scale, int kv_dtype,
+                                       int64_t seq_stride_tokens, const int32_t *seq_lens,
+                                       int H, int D, double scale, int b, int h,
+                                       double *weights, float *out_row)
+{
+    kv_view kv = { k, v, k_scale, v_scale, kv_dtype, D, seq_stride_tokens, NULL, 0, 0 };
+    attend_one(q + ((int64_t)b * H + h) * D, &kv, b, seq_lens[b], scale, out_row, NULL, weights);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Low-rank query path (Section 2): c = x W_qa;                        */
+/* c_hat = c / sqrt(mean(c^2) + eps) * gain;  q = c_hat W_qb.          */
+/* x: bf16 [B, d_model]; w_qa: bf16 [d_model, r]; gain: fp32 [r] or     */
+/* NULL (unit); w_qb: bf16 [r, n_out].  Everything between the inputs   */
+/* and the stored query stays in double; the only rounding is the final */
+/* one to the bf16 storage type.  q_bf16: [B, n_out] (may be NULL);     */
+/* q_f64: [B, n_out] unrounded (may be NULL); c_hat_f64: [B, r] (may be */
+/* NULL).                                                               */
+/* ------------------------------------------------------------------ */
+ORACLE_API int mfa_oracle_query_proj(const uint16_t *x, const uint16_t *w_qa, const float *gain,
+                                     const uint16_t *w_qb, int B, int d_model, int r, int n_out,
+                                     double eps, uint16_t *q_bf16, double *q_f64, double *c_hat_f64)
+{
+    int nthreads = mfa_oracle_get_threads();
+    (void)nthreads;
+    double *wa = (double *)malloc(sizeof(double) * (size_t)d_model * r);
+    double *wb = (double *)malloc(sizeof(double) * (size_t)r * n_out);
+    if (!wa || !wb) { free(wa); free(wb); return 2; }
+    for (int64_t i = 0; i < (int64_t)d_model * r; ++i) wa[i] = decode_bf16(w_qa[i]);
+    for (int64_t i = 0; i < (int64_t)r * n_out; ++i) wb[i] = decode_bf16(w_qb[i]);
+
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int b = 0; b < B; ++b) {
+        double *c = (double *)calloc((size_t)r, sizeof(double));
+        double *qrow = (double *)calloc((size_t)n_out, sizeof(double));
+        for (int i = 0; i < d_model; ++i) {
+            double xi = decode_bf16(x[(int64_t)b * d_model + i]);
+            const double *wrow = wa + (int64_t)i * r;
+            for (int j = 0; j < r; ++j) c[j] += xi * wrow[j];
+        }
+        double ms = 0.0;
+        for (int j = 0; j < r; ++j) ms += c[j] * c[j];
+        ms /= (double)r;
+        double inv = 1.0 / sqrt(ms + eps);
+        for (int j = 0; j < r; ++j) {
+            c[j] = c[j] * inv * (gain ? (double)gain[j] : 1.0);
+            if (c_hat_f64) c_hat_f64[(int64_t)b * r + j] = c[j];
+        }
+        for (int j = 0; j < r; ++j) {
+            const double *wrow = wb + (int64_t)j * n_out;
+            double cj = c[j];
+            for (int n = 0; n < n_out; ++n) qrow[n] += cj * wrow[n];
+        }
+        for (int n = 0; n < n_out; ++n) {
+            if (q_f64) q_f64[(int64_t)b * n_out + n] = qrow[n];
+            if (q_bf16) q_bf16[(int64_t)b * n_out + n] = encode_bf16_rne(qrow[n]);
+        }
+        free(c); free(qrow);
+    }
+    free(wa); free(wb);
+    return 0;
+}
