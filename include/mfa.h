@@ -1,0 +1,181 @@
+/*
+ * mfa.h - C boundary of the MI355X (gfx950) decode-step Multi-Matrix
+ * Factorization Attention (MFA) library.
+ *
+ * The operation is the attention module of the Step-3 paper (Section 2,
+ * "Model Card", and its model-card table): 64 query heads of dimension 256,
+ * produced by a low-rank query factorisation (hidden 7168 -> rank 2048 ->
+ * normalisation -> 64*256), all attend over ONE shared key head and ONE shared
+ * value head of dimension 256.  At decode time every sequence contributes one
+ * query token that attends over all tokens cached for that sequence; a GPU
+ * serves a batch of independent sequences (Section 7.1, local data-parallel
+ * attention).  The cache holds one key row and one value row per token
+ * (Section 6: 512 bytes per token at 8 bits).
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer (HIP global memory on the device
+ *     given at init) unless marked "host".  All tensors are dense, row-major,
+ *     last index fastest, and must be 16-byte aligned.
+ *   - The caller owns every buffer, including the workspace handed to
+ *     mfa_decode_init; the library allocates no device memory, frees nothing
+ *     of the caller's, never synchronises the device or the stream and never
+ *     reads device memory from the host.  All work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Inputs are only read.  Outputs and the workspace are the only writes.
+ *   - Errors are returned as mfa_status; nothing aborts or throws.  Conditions
+ *     the host can see (NULL or misaligned pointers, sizes out of range,
+ *     unsupported shapes or types, fp8 without scales, workspace too small) are
+ *     rejected before anything is launched.  Conditions only the device can see
+ *     have defined results instead: seq_lens[b] <= 0 gives out[b,:,:] = 0;
+ *     seq_lens[b] > max_seq_len_hint is treated as max_seq_len_hint; page ids in
+ *     the block table are trusted.
+ *   - Memory of the cache past a sequence's length (padding, the rest of the
+ *     last page, unused pages) may hold anything, NaN included; it never
+ *     influences the result.
+ *   - A context is not safe for concurrent calls (they share its workspace);
+ *     calls on one context must be ordered on one stream or otherwise
+ *     serialised by the caller.  Distinct contexts are independent.
+ *   - bf16 is bfloat16 (1-8-7).  fp8 is OCP e4m3fn (1-4-3, bias 7, max 448, no
+ *     infinity, 0x7F/0xFF NaN), the native 8-bit float of gfx950.
+ */
+#ifndef MFA_H
+#define MFA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported from libmfa.so (the library is built with hidden default visibility). */
+#define MFA_API __attribute__((visibility("default")))
+
+typedef struct mfa_ctx mfa_ctx;          /* opaque; made by mfa_decode_init */
+
+typedef enum {
+    MFA_OK = 0,
+    MFA_ERR_INVALID_ARG = 1,             /* NULL/misaligned pointer, size out of range      */
+    MFA_ERR_UNSUPPORTED = 2,             /* shape or type this build has no kernel for      */
+    MFA_ERR_WORKSPACE_TOO_SMALL = 3,
+    MFA_ERR_HIP = 4                      /* a HIP runtime call or kernel launch failed      */
+} mfa_status;
+
+typedef enum {
+    MFA_KV_BF16 = 0,
+    MFA_KV_FP8_E4M3 = 1                  /* one fp32 scale per token per tensor             */
+} mfa_kv_dtype;
+
+/* Problem description fixed at init (Section 2, model-card table, gives the
+ * Step-3 values in the comments). */
+typedef struct {
+    int32_t n_q_heads;      /* 64; this build supports exactly 64                          */
+    int32_t head_dim;       /* 256; this build supports exactly 256                        */
+    int32_t d_model;        /* 7168; multiple of 64                                        */
+    int32_t q_rank;         /* 2048; multiple of 128                                       */
+    float   softmax_scale;  /* multiplies q.k before the softmax; 1/16 for head_dim 256    */
+    float   rms_eps;        /* added to the mean square inside the root; 1e-6              */
+    int32_t page_size;      /* tokens per cache page; this build supports exactly 64       */
+    int32_t max_batch;      /* largest B of any later call (attention and query path)      */
+    int32_t max_seq_len;    /* largest max_seq_len_hint of any later call                  */
+    int32_t device;         /* HIP device ordinal                                          */
+} mfa_config;
+
+/* Bytes of device workspace a context for `cfg` needs.  Pure host function;
+ * returns 0 if cfg is NULL or invalid. */
+MFA_API size_t mfa_decode_workspace_bytes(const mfa_config* cfg);
+
+/* Create a context.  `d_workspace` is device memory of at least
+ * mfa_decode_workspace_bytes(cfg) bytes, 256-byte aligned, owned by the caller
+ * and kept alive until mfa_decode_destroy.  Launches nothing. */
+MFA_API mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t workspace_bytes,
+                           mfa_ctx** out_ctx);
+
+/* Free the host-side context (not the workspace).  NULL is allowed. */
+MFA_API void mfa_decode_destroy(mfa_ctx* ctx);
+
+/* Static string for a status code. */
+MFA_API const char* mfa_status_string(mfa_status s);
+
+/*
+ * Low-rank query path (Section 2: the query is down-projected from 7168 to a
+ * rank of 2048, normalised, then up-projected to 64*256):
+ *     c     = x . W_qa                          [B, q_rank]
+ *     c_hat = c / sqrt(mean_j(c_j^2) + rms_eps) * gain
+ *     q     = c_hat . W_qb                      [B, n_q_heads*head_dim]
+ * The paper says only "a normalization"; RMSNorm is this library's reading.
+ *   x        bf16 [B, d_model]
+ *   w_qa     bf16 [d_model, q_rank]             (in x out: y = x.W)
+ *   rms_gain fp32 [q_rank], or NULL for unit gain
+ *   w_qb     bf16 [q_rank, n_q_heads*head_dim]; column h*head_dim + d feeds q[b,h,d]
+ *   q_out    bf16 [B, n_q_heads, head_dim]      (written)
+ * Products are accumulated in fp32; c_hat is rounded to bf16 before the second
+ * product; q is rounded to bf16 once on store.  1 <= B <= max_batch.
+ */
+MFA_API mfa_status mfa_query_proj(mfa_ctx* ctx, const void* x, const void* w_qa, const float* rms_gain,
+                          const void* w_qb, void* q_out, int32_t B, void* hip_stream);
+
+/*
+ * Decode-step attention over a contiguous cache (Section 2: 64 query heads
+ * share one key head and one value head; Section 7.1: independent sequences):
+ *     s[b,h,j] = softmax_scale * sum_d q[b,h,d] * K[b,j,d]        j < seq_lens[b]
+ *     p[b,h,:] = softmax_j(s[b,h,:])
+ *     out[b,h,d] = sum_j p[b,h,j] * V[b,j,d]
+ * with K[b,j,:] = k_cache[b,j,:] for bf16 and k_scale[b,j] * k_cache[b,j,:] for
+ * fp8 (V likewise).
+ *   q        bf16 [B, n_q_heads, head_dim]
+ *   k_cache, v_cache  [B, kv_seq_stride_tokens, head_dim] in kv_dtype
+ *   k_scale, v_scale  fp32 [B, kv_seq_stride_tokens]; NULL unless fp8
+ *   kv_seq_stride_tokens  rows between consecutive sequences (>= max_seq_len_hint)
+ *   seq_lens int32 [B] on the DEVICE (never read by the host)
+ *   max_seq_len_hint  host-side upper bound of seq_lens, used only to size the
+ *            launch; 1 <= hint <= cfg.max_seq_len
+ *   out      fp32 [B, n_q_heads, head_dim]      (written)
+ * Scores and sums are accumulated in fp32; attention weights are rounded to
+ * bf16 before they multiply V.  For a given build, device and arguments the
+ * result is bitwise reproducible from call to call.
+ */
+MFA_API mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                           const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
+                           int64_t kv_seq_stride_tokens, const int32_t* seq_lens,
+                           int32_t max_seq_len_hint, int32_t B, float* out, void* hip_stream);
+
+/*
+ * The same attention over a paged cache: token j of sequence b is row
+ * (j % page_size) of page block_table[b][j / page_size].
+ *   k_pool, v_pool            [n_pages, page_size, head_dim] in kv_dtype
+ *   k_scale_pool, v_scale_pool  fp32 [n_pages, page_size]; NULL unless fp8
+ *   block_table  int32 [B, max_blocks_per_seq] on the device; entries at or past
+ *                ceil(seq_lens[b] / page_size) are never read (may be -1)
+ *   max_blocks_per_seq >= ceil(max_seq_len_hint / page_size)
+ * Other arguments as mfa_decode_attn.  For the same tokens the result is
+ * bitwise equal to mfa_decode_attn's on the gathered contiguous cache with the
+ * same max_seq_len_hint and B.
+ */
+MFA_API mfa_status mfa_decode_attn_paged(mfa_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                                 const float* k_scale_pool, const float* v_scale_pool,
+                                 mfa_kv_dtype kv_dtype, int32_t n_pages, const int32_t* block_table,
+                                 int32_t max_blocks_per_seq, const int32_t* seq_lens,
+                                 int32_t max_seq_len_hint, int32_t B, float* out, void* hip_stream);
+
+/*
+ * Test aid, not part of the serving path: copy the logical cache of every
+ * sequence out of a paged pool into a contiguous buffer
+ *   dst [B, dst_seq_stride_tokens, row_bytes] (bytes; row_bytes = bytes of one
+ *   token row, a multiple of 4), rows j < seq_lens[b] only; other rows untouched.
+ * Used to check that paged addressing moves bytes exactly.
+ */
+MFA_API mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_t row_bytes, int32_t n_pages,
+                                  const int32_t* block_table, int32_t max_blocks_per_seq,
+                                  const int32_t* seq_lens, int32_t max_seq_len_hint, int32_t B,
+                                  void* dst, int64_t dst_seq_stride_tokens, void* hip_stream);
+
+/* Number of context splits the next mfa_decode_attn* call with these host
+ * arguments would use (each split's partial result is merged by the library).
+ * Pure host function; 0 on invalid arguments. */
+MFA_API int32_t mfa_decode_num_splits(const mfa_ctx* ctx, int32_t B, int32_t max_seq_len_hint);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MFA_H */

@@ -1,0 +1,263 @@
+"""Thin ctypes binding of libmfa.so (the C boundary declared in include/mfa.h).
+
+Argument marshalling only: every step of the decode path runs in the HIP
+kernels of the library.  PyTorch supplies device memory (tensors) and the
+current HIP stream.  There is no fallback: if the library cannot be loaded the
+import of a function from it raises.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+from . import build as _build
+
+MFA_OK = 0
+MFA_ERR_INVALID_ARG = 1
+MFA_ERR_UNSUPPORTED = 2
+MFA_ERR_WORKSPACE_TOO_SMALL = 3
+MFA_ERR_HIP = 4
+
+MFA_KV_BF16 = 0
+MFA_KV_FP8_E4M3 = 1
+
+EXPORTS = [
+    "mfa_decode_workspace_bytes", "mfa_decode_init", "mfa_decode_destroy", "mfa_status_string",
+    "mfa_query_proj", "mfa_decode_attn", "mfa_decode_attn_paged", "mfa_debug_gather_paged",
+    "mfa_decode_num_splits",
+]
+
+
+class MfaConfigC(ctypes.Structure):
+    _fields_ = [
+        ("n_q_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("d_model", ctypes.c_int32),
+        ("q_rank", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("rms_eps", ctypes.c_float),
+        ("page_size", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("max_seq_len", ctypes.c_int32),
+        ("device", ctypes.c_int32),
+    ]
+
+
+@dataclass
+class MfaConfig:
+    n_q_heads: int = 64
+    head_dim: int = 256
+    d_model: int = 7168
+    q_rank: int = 2048
+    softmax_scale: float = 1.0 / 16.0
+    rms_eps: float = 1e-6
+    page_size: int = 64
+    max_batch: int = 128
+    max_seq_len: int = 32768
+    device: int = 0
+
+    def to_c(self):
+        return MfaConfigC(self.n_q_heads, self.head_dim, self.d_model, self.q_rank, self.softmax_scale,
+                          self.rms_eps, self.page_size, self.max_batch, self.max_seq_len, self.device)
+
+
+_lib = None
+
+
+def lib_path():
+    return _build.LIB
+
+
+def lib():
+    """Load libmfa.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        _build.build(force=True)
+    L = ctypes.CDLL(path)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    cfgp = ctypes.POINTER(MfaConfigC)
+    L.mfa_decode_workspace_bytes.restype = sz
+    L.mfa_decode_workspace_bytes.argtypes = [cfgp]
+    L.mfa_decode_init.restype = ctypes.c_int
+    L.mfa_decode_init.argtypes = [cfgp, vp, sz, ctypes.POINTER(vp)]
+    L.mfa_decode_destroy.restype = None
+    L.mfa_decode_destroy.argtypes = [vp]
+    L.mfa_status_string.restype = ctypes.c_char_p
+    L.mfa_status_string.argtypes = [ctypes.c_int]
+    L.mfa_query_proj.restype = ctypes.c_int
+    L.mfa_query_proj.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp]
+    L.mfa_decode_attn.restype = ctypes.c_int
+    L.mfa_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i64, vp, i32, i32, vp, vp]
+    L.mfa_decode_attn_paged.restype = ctypes.c_int
+    L.mfa_decode_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, i32, vp, i32, i32, vp, vp]
+    L.mfa_debug_gather_paged.restype = ctypes.c_int
+    L.mfa_debug_gather_paged.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, i64, vp]
+    L.mfa_decode_num_splits.restype = i32
+    L.mfa_decode_num_splits.argtypes = [vp, i32, i32]
+    _lib = L
+    return L
+
+
+class MfaError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().mfa_status_string(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def _check(status, where):
+    if status != MFA_OK:
+        raise MfaError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _kv_dtype(t):
+    if t.dtype == torch.bfloat16:
+        return MFA_KV_BF16
+    if t.dtype == torch.float8_e4m3fn:
+        return MFA_KV_FP8_E4M3
+    raise TypeError(f"unsupported cache dtype {t.dtype}")
+
+
+def _want(t, dtype, name):
+    if t.dtype != dtype or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{name}: expected contiguous device tensor of {dtype}, got {t.dtype} on {t.device}")
+
+
+def mfa_decode_workspace_bytes(cfg: MfaConfig) -> int:
+    c = cfg.to_c()
+    return int(lib().mfa_decode_workspace_bytes(ctypes.byref(c)))
+
+
+class MfaContext:
+    """Owns the device workspace (a torch tensor) and the library context handle."""
+
+    def __init__(self, cfg: MfaConfig):
+        self.cfg = cfg
+        nbytes = mfa_decode_workspace_bytes(cfg)
+        if nbytes == 0:
+            raise MfaError(MFA_ERR_UNSUPPORTED, "mfa_decode_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=f"cuda:{cfg.device}")
+        handle = ctypes.c_void_p()
+        c = cfg.to_c()
+        with torch.cuda.device(cfg.device):
+            _check(lib().mfa_decode_init(ctypes.byref(c), _ptr(self.workspace), nbytes, ctypes.byref(handle)),
+                   "mfa_decode_init")
+        self.handle = handle
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().mfa_decode_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def mfa_decode_init(cfg: MfaConfig) -> MfaContext:
+    return MfaContext(cfg)
+
+
+def mfa_decode_num_splits(ctx: MfaContext, B: int, max_seq_len_hint: int) -> int:
+    return int(lib().mfa_decode_num_splits(ctx.handle, B, max_seq_len_hint))
+
+
+def mfa_query_proj(ctx: MfaContext, x, w_qa, w_qb, rms_gain=None, q_out=None):
+    """x bf16 [B,d_model], w_qa bf16 [d_model,r], w_qb bf16 [r,H*D] -> q bf16 [B,H,D]."""
+    cfg = ctx.cfg
+    for t, nm in ((x, "x"), (w_qa, "w_qa"), (w_qb, "w_qb")):
+        _want(t, torch.bfloat16, nm)
+    B = x.shape[0]
+    if tuple(x.shape) != (B, cfg.d_model) or tuple(w_qa.shape) != (cfg.d_model, cfg.q_rank) or \
+            tuple(w_qb.shape) != (cfg.q_rank, cfg.n_q_heads * cfg.head_dim):
+        raise ValueError("query path shapes do not match the context configuration")
+    if rms_gain is not None:
+        _want(rms_gain, torch.float32, "rms_gain")
+        if tuple(rms_gain.shape) != (cfg.q_rank,):
+            raise ValueError("rms_gain shape")
+    if q_out is None:
+        q_out = torch.empty(B, cfg.n_q_heads, cfg.head_dim, dtype=torch.bfloat16, device=x.device)
+    else:
+        _want(q_out, torch.bfloat16, "q_out")
+    _check(lib().mfa_query_proj(ctx.handle, _ptr(x), _ptr(w_qa), _ptr(rms_gain), _ptr(w_qb), _ptr(q_out), B,
+                                _stream()), "mfa_query_proj")
+    return q_out
+
+
+def mfa_decode_attn(ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_hint, k_scale=None,
+                    v_scale=None, out=None):
+    """q bf16 [B,H,D]; k_cache,v_cache [B,S,D] bf16 or float8_e4m3fn; seq_lens int32 [B] on device."""
+    cfg = ctx.cfg
+    _want(q, torch.bfloat16, "q")
+    _want(seq_lens, torch.int32, "seq_lens")
+    B = q.shape[0]
+    kvd = _kv_dtype(k_cache)
+    if v_cache.dtype != k_cache.dtype or not k_cache.is_contiguous() or not v_cache.is_contiguous():
+        raise TypeError("k_cache / v_cache must be contiguous and of one dtype")
+    S = k_cache.shape[1]
+    if tuple(q.shape) != (B, cfg.n_q_heads, cfg.head_dim) or tuple(k_cache.shape) != (B, S, cfg.head_dim) or \
+            tuple(v_cache.shape) != (B, S, cfg.head_dim) or tuple(seq_lens.shape) != (B,):
+        raise ValueError("attention shapes do not match")
+    for t, nm in ((k_scale, "k_scale"), (v_scale, "v_scale")):
+        if t is not None:
+            _want(t, torch.float32, nm)
+            if tuple(t.shape) != (B, S):
+                raise ValueError(nm + " shape")
+    if out is None:
+        out = torch.empty(B, cfg.n_q_heads, cfg.head_dim, dtype=torch.float32, device=q.device)
+    else:
+        _want(out, torch.float32, "out")
+    _check(lib().mfa_decode_attn(ctx.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
+                                 kvd, S, _ptr(seq_lens), int(max_seq_len_hint), B, _ptr(out), _stream()),
+           "mfa_decode_attn")
+    return out
+
+
+def mfa_decode_attn_paged(ctx: MfaContext, q, k_pool, v_pool, block_table, seq_lens, max_seq_len_hint,
+                          k_scale_pool=None, v_scale_pool=None, out=None):
+    """k_pool,v_pool [n_pages,page,D]; block_table int32 [B,max_blocks] on device."""
+    cfg = ctx.cfg
+    _want(q, torch.bfloat16, "q")
+    _want(seq_lens, torch.int32, "seq_lens")
+    _want(block_table, torch.int32, "block_table")
+    B = q.shape[0]
+    kvd = _kv_dtype(k_pool)
+    if v_pool.dtype != k_pool.dtype or not k_pool.is_contiguous() or not v_pool.is_contiguous():
+        raise TypeError("k_pool / v_pool must be contiguous and of one dtype")
+    n_pages = k_pool.shape[0]
+    if tuple(k_pool.shape) != (n_pages, cfg.page_size, cfg.head_dim) or tuple(v_pool.shape) != tuple(k_pool.shape) \
+            or block_table.shape[0] != B or tuple(seq_lens.shape) != (B,) or \
+            tuple(q.shape) != (B, cfg.n_q_heads, cfg.head_dim):
+        raise ValueError("paged attention shapes do not match")
+    for t, nm in ((k_scale_pool, "k_scale_pool"), (v_scale_pool, "v_scale_pool")):
+        if t is not None:
+            _want(t, torch.float32, nm)
+            if tuple(t.shape) != (n_pages, cfg.page_size):
+                raise ValueError(nm + " shape")
+    if out is None:
+        out = torch.empty(B, cfg.n_q_heads, cfg.head_dim, dtype=torch.float32, device=q.device)
+    else:
+        _want(out, torch.float32, "out")
+    _check(lib().mfa_decode_attn_paged(ctx.handle, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale_pool),
+                                       _ptr(v_scale_pool), kvd, n_pages, _ptr(block_table), block_table.shape[1],
+                                       _ptr(seq_lens), int(max_seq_len_hint), B, _ptr(out), _stream()),
+           "mfa_decode_attn_paged")
+    return out
+
+
+def mfa_debug_gather_paged(ctx: MfaContext, pool, block_table, seq_lens, max_seq_len_hint, dst):
+    """Copy rows j < seq_lens[b] of every sequence from pool [n_pages,page,...] into dst [B,S,...]."""
+    row_bytes = pool[0, 0].numel() * pool.element_size()
+    B = block_table.shape[0]
+    _check(lib().mfa_debug_gather_paged(ctx.handle, _ptr(pool), row_bytes, pool.shape[0], _ptr(block_table),
+                                        block_table.shape[1], _ptr(seq_lens), int(max_seq_len_hint), B, _ptr(dst),
+                                        dst.shape[1], _stream()), "mfa_debug_gather_paged")
+    return dst

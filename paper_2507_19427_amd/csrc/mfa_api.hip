@@ -1,0 +1,269 @@
+// C boundary of libmfa.so: argument checking, workspace carving and dispatch.
+// Every entry point is declared and documented in include/mfa.h.
+#include <cmath>
+#include <cstdlib>
+#include <new>
+
+#include "mfa_internal.hpp"
+
+using namespace mfa;
+
+struct mfa_ctx {
+    mfa_config cfg;
+    int32_t target_items;      // work items the split planner aims for (one per compute unit by default)
+    size_t max_items;          // bound on B * n_splits over all admissible calls
+    float* ws_acc;
+    float* ws_ml;
+    float* ws_c;
+    void* ws_chat;
+    int32_t qproj_split_k;
+    int32_t qproj_rows_pad;
+};
+
+namespace {
+
+constexpr int32_t kDefaultTargetItems = 256;   // MI355X has 256 compute units; one workgroup fills one
+
+int32_t target_items_from_env()
+{
+    const char* s = std::getenv("MFA_TARGET_ITEMS");
+    if (s) {
+        const long v = std::strtol(s, nullptr, 10);
+        if (v >= 1 && v <= 4096) return (int32_t)v;
+    }
+    return kDefaultTargetItems;
+}
+
+bool config_ok(const mfa_config* c)
+{
+    if (!c) return false;
+    if (c->max_batch < 1 || c->max_batch > 65536) return false;
+    if (c->max_seq_len < 1 || c->max_seq_len > (1 << 24)) return false;
+    if (c->d_model < 64 || c->d_model % 64) return false;
+    if (c->q_rank < 128 || c->q_rank % 128) return false;
+    if (!(c->softmax_scale > 0.f) || !std::isfinite(c->softmax_scale)) return false;
+    if (!(c->rms_eps >= 0.f) || !std::isfinite(c->rms_eps)) return false;
+    if (c->device < 0) return false;
+    return true;
+}
+
+bool config_supported(const mfa_config* c)
+{
+    return c->n_q_heads == kHeads && c->head_dim == kHeadDim && c->page_size == kPage;
+}
+
+size_t max_items_for(const mfa_config* c, int32_t target)
+{
+    size_t best = 0;
+    for (int32_t B = 1; B <= c->max_batch; ++B) {
+        const SplitPlan p = plan_splits(B, c->max_seq_len, target);
+        const size_t items = (size_t)B * p.n_splits;
+        if (items > best) best = items;
+    }
+    return best;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Carve {
+    size_t acc, ml, c, chat, total;
+    size_t max_items;
+    int32_t split_k, rows_pad;
+};
+
+Carve carve(const mfa_config* c, int32_t target)
+{
+    Carve w;
+    w.max_items = max_items_for(c, target);
+    w.split_k = qproj_split_k(c->d_model);
+    w.rows_pad = (c->max_batch + kQProjRows - 1) / kQProjRows * kQProjRows;
+    size_t off = 0;
+    w.acc = off; off = align_up(off + w.max_items * kPartialAccFloats * sizeof(float), 256);
+    w.ml = off;  off = align_up(off + w.max_items * kPartialMlFloats * sizeof(float), 256);
+    w.c = off;   off = align_up(off + (size_t)w.split_k * w.rows_pad * c->q_rank * sizeof(float), 256);
+    w.chat = off; off = align_up(off + (size_t)w.rows_pad * c->q_rank * 2, 256);
+    w.total = off;
+    return w;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool on_device(const mfa_ctx* ctx)
+{
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess && dev == ctx->cfg.device;
+}
+
+mfa_status check_attn_common(const mfa_ctx* ctx, const void* q, const void* k, const void* v, const float* ks,
+                             const float* vs, mfa_kv_dtype kv_dtype, const int32_t* seq_lens, int32_t hint,
+                             int32_t B, const float* out)
+{
+    if (!ctx || !q || !k || !v || !seq_lens || !out) return MFA_ERR_INVALID_ARG;
+    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return MFA_ERR_INVALID_ARG;
+    if (kv_dtype == MFA_KV_FP8_E4M3 && (!ks || !vs)) return MFA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(ks) || !aligned16(vs) ||
+        (reinterpret_cast<uintptr_t>(seq_lens) & 3u))
+        return MFA_ERR_INVALID_ARG;
+    if (B < 1 || B > ctx->cfg.max_batch) return MFA_ERR_INVALID_ARG;
+    if (hint < 1 || hint > ctx->cfg.max_seq_len) return MFA_ERR_INVALID_ARG;
+    if (!on_device(ctx)) return MFA_ERR_INVALID_ARG;
+    return MFA_OK;
+}
+
+void fill_common(const mfa_ctx* ctx, AttnArgs& a, int32_t B, int32_t hint)
+{
+    const SplitPlan p = plan_splits(B, hint, ctx->target_items);
+    a.n_splits = p.n_splits;
+    a.chunk_tokens = p.chunk_tokens;
+    a.B = B;
+    a.max_seq_len_hint = hint;
+    a.ws_acc = ctx->ws_acc;
+    a.ws_ml = ctx->ws_ml;
+    a.scale_log2e = ctx->cfg.softmax_scale * 1.44269504088896340736f;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mfa_decode_workspace_bytes(const mfa_config* cfg)
+{
+    if (!config_ok(cfg) || !config_supported(cfg)) return 0;
+    return carve(cfg, target_items_from_env()).total;
+}
+
+mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t workspace_bytes, mfa_ctx** out_ctx)
+{
+    if (out_ctx) *out_ctx = nullptr;
+    if (!out_ctx || !config_ok(cfg) || !d_workspace) return MFA_ERR_INVALID_ARG;
+    if (!config_supported(cfg)) return MFA_ERR_UNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return MFA_ERR_INVALID_ARG;
+    const int32_t target = target_items_from_env();
+    const Carve w = carve(cfg, target);
+    if (workspace_bytes < w.total) return MFA_ERR_WORKSPACE_TOO_SMALL;
+
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess) return MFA_ERR_HIP;
+    if (cfg->device >= n_dev) return MFA_ERR_INVALID_ARG;
+    int prev = -1;
+    if (hipGetDevice(&prev) != hipSuccess) return MFA_ERR_HIP;
+    if (prev != cfg->device && hipSetDevice(cfg->device) != hipSuccess) return MFA_ERR_HIP;
+    const hipError_t e = prepare_decode_attn_kernels();
+    if (prev != cfg->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) return MFA_ERR_HIP;
+
+    mfa_ctx* ctx = new (std::nothrow) mfa_ctx;
+    if (!ctx) return MFA_ERR_INVALID_ARG;
+    ctx->cfg = *cfg;
+    ctx->target_items = target;
+    ctx->max_items = w.max_items;
+    unsigned char* base = static_cast<unsigned char*>(d_workspace);
+    ctx->ws_acc = reinterpret_cast<float*>(base + w.acc);
+    ctx->ws_ml = reinterpret_cast<float*>(base + w.ml);
+    ctx->ws_c = reinterpret_cast<float*>(base + w.c);
+    ctx->ws_chat = base + w.chat;
+    ctx->qproj_split_k = w.split_k;
+    ctx->qproj_rows_pad = w.rows_pad;
+    *out_ctx = ctx;
+    return MFA_OK;
+}
+
+void mfa_decode_destroy(mfa_ctx* ctx) { delete ctx; }
+
+const char* mfa_status_string(mfa_status s)
+{
+    switch (s) {
+        case MFA_OK: return "ok";
+        case MFA_ERR_INVALID_ARG: return "invalid argument";
+        case MFA_ERR_UNSUPPORTED: return "unsupported shape or type";
+        case MFA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case MFA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int32_t mfa_decode_num_splits(const mfa_ctx* ctx, int32_t B, int32_t max_seq_len_hint)
+{
+    if (!ctx || B < 1 || B > ctx->cfg.max_batch || max_seq_len_hint < 1 || max_seq_len_hint > ctx->cfg.max_seq_len)
+        return 0;
+    return plan_splits(B, max_seq_len_hint, ctx->target_items).n_splits;
+}
+
+mfa_status mfa_query_proj(mfa_ctx* ctx, const void* x, const void* w_qa, const float* rms_gain, const void* w_qb,
+                          void* q_out, int32_t B, void* hip_stream)
+{
+    if (!ctx || !x || !w_qa || !w_qb || !q_out) return MFA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_qa) || !aligned16(w_qb) || !aligned16(q_out) || !aligned16(rms_gain))
+        return MFA_ERR_INVALID_ARG;
+    if (B < 1 || B > ctx->cfg.max_batch) return MFA_ERR_INVALID_ARG;
+    if (!on_device(ctx)) return MFA_ERR_INVALID_ARG;
+    QProjArgs a;
+    a.x = x; a.w_qa = w_qa; a.gain = rms_gain; a.w_qb = w_qb; a.q_out = q_out;
+    a.ws_c = ctx->ws_c; a.ws_chat = ctx->ws_chat;
+    a.B = B; a.d_model = ctx->cfg.d_model; a.q_rank = ctx->cfg.q_rank;
+    a.n_out = ctx->cfg.n_q_heads * ctx->cfg.head_dim;
+    a.split_k = ctx->qproj_split_k;
+    a.eps = ctx->cfg.rms_eps;
+    return launch_query_proj(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                           const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
+                           int64_t kv_seq_stride_tokens, const int32_t* seq_lens, int32_t max_seq_len_hint,
+                           int32_t B, float* out, void* hip_stream)
+{
+    const mfa_status st = check_attn_common(ctx, q, k_cache, v_cache, k_scale, v_scale, kv_dtype, seq_lens,
+                                            max_seq_len_hint, B, out);
+    if (st != MFA_OK) return st;
+    if (kv_seq_stride_tokens < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
+    AttnArgs a{};
+    a.q = q; a.k = k_cache; a.v = v_cache; a.k_scale = k_scale; a.v_scale = v_scale;
+    a.seq_lens = seq_lens; a.block_table = nullptr; a.out = out;
+    a.seq_stride_tokens = kv_seq_stride_tokens; a.max_blocks_per_seq = 0;
+    fill_common(ctx, a, B, max_seq_len_hint);
+    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorNotSupported) return MFA_ERR_UNSUPPORTED;
+    return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+mfa_status mfa_decode_attn_paged(mfa_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                                 const float* k_scale_pool, const float* v_scale_pool, mfa_kv_dtype kv_dtype,
+                                 int32_t n_pages, const int32_t* block_table, int32_t max_blocks_per_seq,
+                                 const int32_t* seq_lens, int32_t max_seq_len_hint, int32_t B, float* out,
+                                 void* hip_stream)
+{
+    const mfa_status st = check_attn_common(ctx, q, k_pool, v_pool, k_scale_pool, v_scale_pool, kv_dtype, seq_lens,
+                                            max_seq_len_hint, B, out);
+    if (st != MFA_OK) return st;
+    if (!block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u) || n_pages < 1) return MFA_ERR_INVALID_ARG;
+    if ((int64_t)max_blocks_per_seq * kPage < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
+    AttnArgs a{};
+    a.q = q; a.k = k_pool; a.v = v_pool; a.k_scale = k_scale_pool; a.v_scale = v_scale_pool;
+    a.seq_lens = seq_lens; a.block_table = block_table; a.out = out;
+    a.seq_stride_tokens = 0; a.max_blocks_per_seq = max_blocks_per_seq;
+    fill_common(ctx, a, B, max_seq_len_hint);
+    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorNotSupported) return MFA_ERR_UNSUPPORTED;
+    return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_t row_bytes, int32_t n_pages,
+                                  const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* seq_lens,
+                                  int32_t max_seq_len_hint, int32_t B, void* dst, int64_t dst_seq_stride_tokens,
+                                  void* hip_stream)
+{
+    if (!ctx || !pool || !block_table || !seq_lens || !dst) return MFA_ERR_INVALID_ARG;
+    if (row_bytes < 4 || row_bytes % 4 || n_pages < 1) return MFA_ERR_INVALID_ARG;
+    if (B < 1 || B > ctx->cfg.max_batch) return MFA_ERR_INVALID_ARG;
+    if (max_seq_len_hint < 1 || max_seq_len_hint > ctx->cfg.max_seq_len) return MFA_ERR_INVALID_ARG;
+    if ((int64_t)max_blocks_per_seq * kPage < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
+    if (dst_seq_stride_tokens < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(pool) & 3u) || (reinterpret_cast<uintptr_t>(dst) & 3u)) return MFA_ERR_INVALID_ARG;
+    if (!on_device(ctx)) return MFA_ERR_INVALID_ARG;
+    const hipError_t e = launch_gather_paged(pool, row_bytes, block_table, max_blocks_per_seq, seq_lens,
+                                             max_seq_len_hint, B, dst, dst_seq_stride_tokens,
+                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Internal declarations shared by the translation units of libmfa.so (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/mfa.h"
+
+namespace mfa {
+
+constexpr int kHeads = 64;       // query heads sharing one key head and one value head
+constexpr int kHeadDim = 256;
+constexpr int kPage = 64;        // tokens per cache page = tokens per streamed tile
+constexpr int kTile = 64;
+
+// Vector types for MFMA operands.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// How the context of one call is cut into work items.  Pure host arithmetic.
+struct SplitPlan {
+    int32_t n_splits;       // work items per sequence
+    int32_t chunk_tokens;   // tokens per work item, a multiple of kTile
+};
+SplitPlan plan_splits(int32_t B, int32_t max_seq_len_hint, int32_t target_items);
+
+// Per work item the split kernel leaves: acc [kHeads][kHeadDim] fp32 (unnormalised),
+// and (m, l) per head: running maximum in the log2 domain and the sum of weights.
+constexpr size_t kPartialAccFloats = (size_t)kHeads * kHeadDim;
+constexpr size_t kPartialMlFloats = (size_t)kHeads * 2;
+
+struct AttnArgs {
+    const void* q;                 // bf16 [B,64,256]
+    const void* k;                 // cache or pool
+    const void* v;
+    const float* k_scale;          // fp8 only
+    const float* v_scale;
+    const int32_t* seq_lens;       // device
+    const int32_t* block_table;    // device, NULL for contiguous
+    float* out;                    // fp32 [B,64,256]
+    float* ws_acc;                 // [B*n_splits][64][256]
+    float* ws_ml;                  // [B*n_splits][64][2]
+    int64_t seq_stride_tokens;     // contiguous only
+    int32_t max_blocks_per_seq;    // paged only
+    int32_t B;
+    int32_t n_splits;
+    int32_t chunk_tokens;
+    int32_t max_seq_len_hint;
+    float scale_log2e;             // softmax_scale * log2(e)
+};
+
+// Launchers (enqueue only; return the launch status).
+hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream);
+hipError_t prepare_decode_attn_kernels();   // one-time function attributes (dynamic LDS size)
+
+struct QProjArgs {
+    const void* x;        // bf16 [B,d_model]
+    const void* w_qa;     // bf16 [d_model,q_rank]
+    const float* gain;    // fp32 [q_rank] or NULL
+    const void* w_qb;     // bf16 [q_rank,n_out]
+    void* q_out;          // bf16 [B,n_out]
+    float* ws_c;          // fp32 [split_k][B_pad][q_rank] partial sums of the first product
+    void* ws_chat;        // bf16 [B_pad][q_rank]
+    int32_t B, d_model, q_rank, n_out;
+    int32_t split_k;
+    float eps;
+};
+constexpr int kQProjRows = 128;   // rows of x one workgroup column covers
+int32_t qproj_split_k(int32_t d_model);
+hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream);
+
+hipError_t launch_gather_paged(const void* pool, int32_t row_bytes, const int32_t* block_table,
+                               int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t max_seq_len_hint,
+                               int32_t B, void* dst, int64_t dst_seq_stride_tokens, hipStream_t stream);
+
+}  // namespace mfa

@@ -1,0 +1,89 @@
+"""Host-side checks of the C boundary that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_19427_amd import binding as B
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "mfa.h")
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"MFA_API\s+[\w\s\*]+?\b(mfa_\w+)\s*\(", text)
+
+
+def test_header_declares_the_contract_entry_points():
+    names = _declared()
+    for must in ("mfa_decode_init", "mfa_query_proj", "mfa_decode_attn", "mfa_decode_attn_paged"):
+        assert must in names
+    assert sorted(names) == sorted(B.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    for name in _declared():
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    L = B.lib()
+    assert L.mfa_status_string(0) == b"ok"
+    assert len({L.mfa_status_string(i) for i in range(5)}) == 5
+
+
+def test_workspace_bytes_is_a_pure_host_function():
+    cfg = B.MfaConfig()
+    n = B.mfa_decode_workspace_bytes(cfg)
+    # partial results for at least one work item per compute unit, plus the query path scratch
+    assert n >= 256 * (64 * 256 + 128) * 4 + 128 * 2048 * 4
+    assert n % 256 == 0
+    bigger = B.mfa_decode_workspace_bytes(B.MfaConfig(max_batch=512))
+    assert bigger > n
+    assert B.mfa_decode_workspace_bytes(B.MfaConfig(head_dim=128)) == 0      # unsupported shape
+    assert B.mfa_decode_workspace_bytes(B.MfaConfig(max_batch=0)) == 0
+    assert B.lib().mfa_decode_workspace_bytes(None) == 0
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_q_heads=32), B.MFA_ERR_UNSUPPORTED),
+    (dict(head_dim=128), B.MFA_ERR_UNSUPPORTED),
+    (dict(page_size=16), B.MFA_ERR_UNSUPPORTED),
+    (dict(max_batch=0), B.MFA_ERR_INVALID_ARG),
+    (dict(max_seq_len=0), B.MFA_ERR_INVALID_ARG),
+    (dict(softmax_scale=float("nan")), B.MFA_ERR_INVALID_ARG),
+    (dict(d_model=100), B.MFA_ERR_INVALID_ARG),
+])
+def test_init_rejects_bad_configs_before_any_device_call(kw, status):
+    L = B.lib()
+    c = B.MfaConfig(**kw).to_c()
+    handle = ctypes.c_void_p(123)
+    fake_ws = ctypes.c_void_p(4096)          # never dereferenced: the config is checked first
+    assert L.mfa_decode_init(ctypes.byref(c), fake_ws, 1 << 40, ctypes.byref(handle)) == status
+    assert handle.value is None
+
+
+def test_init_rejects_null_misaligned_and_small_workspace():
+    L = B.lib()
+    c = B.MfaConfig().to_c()
+    handle = ctypes.c_void_p()
+    assert L.mfa_decode_init(ctypes.byref(c), None, 1 << 40, ctypes.byref(handle)) == B.MFA_ERR_INVALID_ARG
+    assert L.mfa_decode_init(ctypes.byref(c), ctypes.c_void_p(4096 + 16), 1 << 40, ctypes.byref(handle)) == B.MFA_ERR_INVALID_ARG
+    assert L.mfa_decode_init(ctypes.byref(c), ctypes.c_void_p(4096), 1024, ctypes.byref(handle)) == B.MFA_ERR_WORKSPACE_TOO_SMALL
+    assert L.mfa_decode_init(ctypes.byref(c), ctypes.c_void_p(4096), 1 << 40, None) == B.MFA_ERR_INVALID_ARG
+    assert L.mfa_decode_init(None, ctypes.c_void_p(4096), 1 << 40, ctypes.byref(handle)) == B.MFA_ERR_INVALID_ARG
+
+
+def test_calls_reject_a_null_context():
+    L = B.lib()
+    p = ctypes.c_void_p(4096)
+    assert L.mfa_decode_attn(None, p, p, p, None, None, 0, 64, p, 64, 1, p, None) == B.MFA_ERR_INVALID_ARG
+    assert L.mfa_decode_attn_paged(None, p, p, p, None, None, 0, 1, p, 1, p, 64, 1, p, None) == B.MFA_ERR_INVALID_ARG
+    assert L.mfa_query_proj(None, p, p, None, p, p, 1, None) == B.MFA_ERR_INVALID_ARG
+    assert L.mfa_debug_gather_paged(None, p, 512, 1, p, 1, p, 64, 1, p, 64, None) == B.MFA_ERR_INVALID_ARG
+    assert L.mfa_decode_num_splits(None, 1, 64) == 0
+    L.mfa_decode_destroy(None)

@@ -1,0 +1,63 @@
+"""The named workloads at their full size, in the launch configuration the benchmark times:
+sampled (sequence, head) rows against the oracle, plus properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_19427_amd as mfa
+from paper_2507_19427_amd import workloads as W
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_sampled(case, got, n_rows, tol):
+    rows = U.sample_rows(case, n_rows)
+    ref = U.run_oracle(case, rows=rows)
+    sub = np.stack([got[b, h] for b, h in rows])
+    err = U.row_normalised_error(sub, ref)
+    print(f"[{case.name}] sampled rows {len(rows)}: row-normalised max error {err:.3e}", flush=True)
+    assert err <= tol
+
+
+def _check_convex(case_v, lens, got):
+    """Every output element lies between the min and max of its value column."""
+    for b in (0, len(lens) - 1):
+        L = int(lens[b])
+        v = case_v(b, L)
+        assert (got[b] <= v.max(0) + 1e-5).all() and (got[b] >= v.min(0) - 1e-5).all()
+
+
+def test_config2_b64_ctx4096():
+    print("\n[case] cfg2 B=64 ctx=4096 bf16 contiguous", flush=True)
+    case = W.config2_step3(poison=False)
+    ctx = U.get_ctx()
+    assert mfa.mfa_decode_num_splits(ctx, 64, 4096) == 4
+    got = U.run_gpu(ctx, case)
+    assert np.isfinite(got).all()
+    _check_sampled(case, got, 96, U.TOL_BF16)
+    _check_convex(lambda b, L: case.v[b, :L].float().numpy(), case.seq_lens, got)
+    again = U.run_gpu(ctx, case)
+    assert np.array_equal(got, again)
+
+
+def test_config3_ragged_paged():
+    print("\n[case] cfg3 128 ragged paged sequences", flush=True)
+    case = W.config3_ragged_paged(poison=True)
+    assert case.B == 128 and int(case.seq_lens.min()) >= 1024 and int(case.seq_lens.max()) <= 8192
+    ctx = U.get_ctx()
+    got = U.run_gpu(ctx, case, hint=8192)
+    assert np.isfinite(got).all()
+    _check_sampled(case, got, 64, U.TOL_BF16)
+
+
+def test_config4_b16_ctx32768():
+    print("\n[case] cfg4 B=16 ctx=32768 bf16 contiguous", flush=True)
+    case = W.config4_long(poison=False)
+    ctx = U.get_ctx()
+    assert mfa.mfa_decode_num_splits(ctx, 16, 32768) == 16
+    got = U.run_gpu(ctx, case)
+    assert np.isfinite(got).all()
+    _check_sampled(case, got, 32, U.TOL_BF16)
+    _check_convex(lambda b, L: case.v[b, :L].float().numpy(), case.seq_lens, got)
