@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-step MFA attention on one MI355X.
+
+Workload (benchmark configs[1]): batch 64, 64 query heads, one shared K/V head, head dim 256,
+every sequence at context 4096, contiguous bf16 cache, synthetic N(0,1) values from a fixed seed.
+A step is one mfa_decode_attn call (stream the cache once, scores, online softmax, weighted sum,
+merge of the context splits).  Inputs are resident in HBM before the timed region; the cache is
+rotated over several distinct buffer sets so that the 256 MB memory-side cache cannot serve it.
+
+Prints ONE JSON line: metric/value = KV tokens per second, plus
+  roofline      HBM roofline of the attention kernel from HIP-event timings taken in the timed region
+  cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published peak
+KV_BYTES_PER_TOKEN = 1024      # bf16: 256 key + 256 value elements, 2 bytes each
+Q_BYTES_PER_SEQ = 64 * 256 * 2
+OUT_BYTES_PER_SEQ = 64 * 256 * 4
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--buffer-sets", type=int, default=5, help="distinct KV buffer sets rotated through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU's share of the data-parallel decode path; "
+              "--gpus above 1 is not supported (every GPU would run this same kernel on its own sequences).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2507_19427_amd as mfa
+    from paper_2507_19427_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    case = W.config2_step3(poison=False)
+    B, S = case.B, case.k.shape[1]
+    T = case.kv_tokens
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=S))
+    n_splits = mfa.mfa_decode_num_splits(ctx, B, S)
+
+    q = case.q.cuda()
+    lens = case.seq_lens.cuda()
+    n_sets = max(1, args.buffer_sets)
+    k_sets = [case.k.cuda()]
+    v_sets = [case.v.cuda()]
+    for i in range(1, n_sets):                       # further sets: the same values, rolled along the batch axis
+        k_sets.append(torch.roll(k_sets[0], shifts=i, dims=0).contiguous())
+        v_sets.append(torch.roll(v_sets[0], shifts=i, dims=0).contiguous())
+    out = torch.empty(B, 64, 256, dtype=torch.float32, device="cuda")
+
+    def step(i):
+        j = i % n_sets
+        mfa.mfa_decode_attn(ctx, q, k_sets[j], v_sets[j], lens, S, out=out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        starts[i].record()
+        step(i)
+        stops[i].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    ev_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
+    ev_mean = sum(ev_ms) / K
+    ev_median = ev_ms[K // 2]
+
+    value = T / (ms_per_step * 1e-3)
+    algo_bytes = T * KV_BYTES_PER_TOKEN + B * (Q_BYTES_PER_SEQ + OUT_BYTES_PER_SEQ)
+    achieved = algo_bytes / (ev_mean * 1e-3) / 1e9
+    result = {
+        "metric": "KV tokens/s, MFA decode attention, B=64, ctx 4096, bf16, 1 GPU",
+        "value": value,
+        "unit": "KV tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: B=64, 64 q heads, 1 shared K/V head, head_dim 256, ctx 4096, "
+                               "contiguous bf16 KV", "kv_tokens_per_step": T, "n_splits": n_splits,
+                   "kv_buffer_sets": n_sets},
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "mfa_decode_attn call (decode_bf16_kernel + merge_splits_kernel when split)",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "algorithmic_bytes_per_launch": algo_bytes,
+            "event_ms_mean": ev_mean,
+            "event_ms_median": ev_median,
+            "event_ms_min": ev_ms[0],
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(case, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+    ctx.close()
+
+
+def cpu_baseline(case, target_seconds):
+    """Time the CPU oracle, as it stands, on the first sequences of the same workload."""
+    import numpy as np
+    from oracle import mfa_oracle as O
+    b = O.bits_of
+    threads = O.get_threads()
+    S = case.k.shape[1]
+
+    def run(n_seq):
+        sub_lens = case.seq_lens[:n_seq].numpy()
+        t0 = time.perf_counter()
+        O.decode_attn(b(case.q[:n_seq]), b(case.k[:n_seq]), b(case.v[:n_seq]), sub_lens, case.scale)
+        return time.perf_counter() - t0
+
+    t1 = run(1)                                        # calibration: one sequence, all 64 heads
+    n = int(max(1, min(case.B, round(target_seconds / max(t1, 1e-3)))))
+    t = run(n) if n > 1 else t1
+    tokens = int(case.seq_lens[:n].sum())
+    return {
+        "value": tokens / t,
+        "unit": "KV tokens/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"first {n} of {case.B} sequences of the same workload (all 64 heads, ctx {S}), "
+                  f"{tokens} KV tokens in {t:.2f} s",
+    }
+
+
+if __name__ == "__main__":
+    main()
