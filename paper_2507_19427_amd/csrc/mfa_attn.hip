@@ -3,64 +3,53 @@
 // per sequence, independent sequences (Section 7.1).
 //
 // Work decomposition.  A work item is (sequence b, context split s): it streams
-// the tokens [s*chunk, min(L_b, (s+1)*chunk)) once from HBM and leaves either the
-// final output (one split) or an unnormalised partial (acc, m, l) that
-// merge_splits_kernel reduces.  One workgroup of 8 waves per work item:
-//   wave = 4*grp + wq;  wq picks 16 of the 64 heads, grp picks which 32-token
-//   half of every 64-token tile the wave processes.  The two waves that share a
-//   SIMD (same wq, different grp) keep independent online-softmax states that
-//   are merged through LDS at the end, so one can run MFMA while the other runs
-//   its softmax.
-// Tiles of 64 tokens (= one cache page) are brought in with 16-byte
-// global->LDS direct loads into a two-slot ring; slot = K rows then V rows,
-// 512 B per row, 64 KB per slot.  Within a row the 16-byte (K) or 32-byte (V)
-// chunks are XOR-swizzled with the row number so that the MFMA operand reads
-// (16 rows x 16 B for K, 16 rows x 32 B transposing reads for V) spread over all
-// LDS banks.  The swizzle is applied on the global side of the direct load
-// because its LDS side is fixed to base + 16*lane.
+// the tokens [s*chunk, min(L_b, (s+1)*chunk)) once from HBM.  With one split it
+// writes the final output; otherwise it leaves an unnormalised partial
+// (acc, m, l) in the workspace that merge_splits_kernel reduces in split order.
+// One workgroup of 8 waves per work item; mfa_attn_core.hpp describes how the
+// waves share a tile and the MFMA operand layouts.
 //
-// MFMA shapes (v_mfma_f32_16x16x32_bf16; lane = 16*g + n):
-//   scores   S^T[token, head] = K[token, :] . Q[head, :]^T     A = K rows, B = Q
-//            lane holds S^T[token 4g+i, head n], i = 0..3, for each 16-token block
-//   output   O^T[d, head] += V^T[d, token] . P^T[token, head]  A = V^T, B = P
-//            lane holds O^T[d = 16*db + 4g + i, head n]
-// The score block a lane ends up with is exactly the B-operand slice it must
-// supply for the second product (8 tokens of its own head), so attention weights
-// never move between lanes; per-head statistics live in the lanes of that head.
-#include "mfa_internal.hpp"
+// bf16 cache: tiles of 64 tokens (= one cache page) are brought in with 16-byte
+// global->LDS direct loads into a two-slot ring (64 KB per slot: two 32-token
+// unit images).  The XOR swizzle of the unit image is applied on the global side
+// of the direct load because its LDS side is fixed to base + 16*lane.
+//
+// fp8 cache (OCP e4m3, one fp32 scale per token per tensor): the codes and scales
+// of a tile are brought in the same way into a two-slot staging ring (33 KB per
+// slot); the whole workgroup then converts the codes once to bf16 (exact) into a
+// single bf16 tile image, and the same MFMA path runs on it.  The key scale
+// multiplies the score column of its token, the value scale rides on the
+// attention weight of its token.
+#include "mfa_attn_core.hpp"
 
 namespace mfa {
 
-#define LDS_PTR(T, byte_off) ((__attribute__((address_space(3))) T*)(lds_base + (byte_off)))
+constexpr int kSlotBytes = 2 * kUnitBytes;            // one 64-token tile: two unit images
+constexpr int kAttnLdsBytes = 2 * kSlotBytes;         // bf16 kernel: 128 KB
 
-constexpr int kSlotBytes = 65536;        // K 64x512 B then V 64x512 B
-constexpr int kVOffset = 32768;
-constexpr int kAttnLdsBytes = 2 * kSlotBytes;
-constexpr int kAttnThreads = 512;
+constexpr int kStageK = 0;                            // fp8 staging slot: K codes 64x256 B
+constexpr int kStageV = 16384;                        //                   V codes 64x256 B
+constexpr int kStageKScale = 32768;                   //                   64 fp32 key scales
+constexpr int kStageVScale = 33024;                   //                   64 fp32 value scales
+constexpr int kStageBytes = 33792;
+constexpr int kFp8StageBase = kSlotBytes;             // staging ring sits after the bf16 tile image
+constexpr int kFp8LdsBytes = kSlotBytes + 2 * kStageBytes;   // 133120
 
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0) only
-
-// 16 bytes per lane from global memory straight into LDS at lds_addr + 16*lane (lds_addr is
-// wave-uniform and travels in M0).  Issued as inline assembly so that the compiler does not
-// treat later LDS reads of the *other* ring slot as dependent on it; completion is awaited
-// explicitly with wait_vmem_all() followed by a workgroup barrier.  M0 is not otherwise live
-// in these kernels.  The s_nop covers the one wait state required between writing M0 and an
-// LDS-direct load.
-__device__ __forceinline__ void load_to_lds_16B(const void* gptr, uint32_t lds_addr)
+template <bool PAGED>
+__device__ __forceinline__ int64_t tile_row0(const AttnArgs& a, int b, int tile_t0)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(gptr), "s"(lds_addr) : "memory");
+    if (PAGED) {
+        const int page = a.block_table[(size_t)b * a.max_blocks_per_seq + tile_t0 / kPage];
+        return (int64_t)page * kPage;
+    }
+    return (int64_t)b * a.seq_stride_tokens + tile_t0;
 }
 
 template <bool PAGED>
 __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    __attribute__((address_space(3))) unsigned char* lds_base =
-        (__attribute__((address_space(3))) unsigned char*)smem;
-
+    const lds_ptr_t lds_base = (lds_ptr_t)smem;
     const uint32_t lds_addr0 = (uint32_t)(uintptr_t)lds_base;
 
     const int lane = threadIdx.x & 63;
@@ -71,195 +60,153 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     const int g = lane >> 4;
 
     const int item = blockIdx.x;
-    const int b = item / a.n_splits;
-    const int split = item - b * a.n_splits;
-    int L = a.seq_lens[b];
-    L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
-    const int t0 = split * a.chunk_tokens;
-    const int t1 = (t0 + a.chunk_tokens < L) ? t0 + a.chunk_tokens : L;
-    const int head = 16 * wq + n;
+    const ItemRange r = item_range(a, item);
+    if (r.t0 >= r.t1) { empty_item(a, r); return; }
 
-    if (t0 >= t1) {
-        // nothing cached for this item; an empty sequence yields zeros
-        if (a.n_splits == 1) {
-            float4* o = (float4*)(a.out + (size_t)b * kHeads * kHeadDim);
-            for (int i = threadIdx.x; i < kHeads * kHeadDim / 4; i += kAttnThreads) o[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-        return;
-    }
-    const int n_tiles = (t1 - t0 + kTile - 1) / kTile;
-
-    // Query fragments: B operand of the score product, d = 32*ks + 8*g + j.
     bf16x8 qf[8];
-    {
-        const bf16x8* qp = (const bf16x8*)((const uint16_t*)a.q + ((size_t)b * kHeads + head) * kHeadDim + 8 * g);
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[ks] = qp[ks * 4];
-    }
+    load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
 
-    // Direct global->LDS load of one 64-token tile; wave w brings rows [8w, 8w+8) of K and of V.
+    // Wave w brings rows [8w, 8w+8) of the tile's K and V: all in unit w/4.  Rows at or past t1
+    // re-read the last valid token, so nothing outside the sequence is touched and every LDS row
+    // holds finite data (the weights of those rows are masked to zero).
     auto issue_tile = [&](int tile, int slot) {
-        const int tile_t0 = t0 + tile * kTile;
-        int64_t row0;
-        if (PAGED) {
-            const int page = a.block_table[(size_t)b * a.max_blocks_per_seq + tile_t0 / kPage];
-            row0 = (int64_t)page * kPage;
-        } else {
-            row0 = (int64_t)b * a.seq_stride_tokens + tile_t0;
-        }
+        const int tile_t0 = r.t0 + tile * kTile;
+        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0);
         const int p16 = lane & 31;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int row = 8 * wave + 2 * u + (lane >> 5);          // row of the tile this lane fills
             int in_tile = row;
-            if (tile_t0 + row > t1 - 1) in_tile = t1 - 1 - tile_t0;  // past the end: re-read the last valid token
+            if (tile_t0 + row > r.t1 - 1) in_tile = r.t1 - 1 - tile_t0;
             const size_t grow = (size_t)(row0 + in_tile) * 512;
-            const int ck = p16 ^ (row & 15);
-            const int cv = ((((p16 >> 1) ^ (row & 15)) << 1) | (p16 & 1));
+            const int key = row & 15;
+            const int ck = p16 ^ key;
+            const int cv = ((((p16 >> 1) ^ key) << 1) | (p16 & 1));
             const unsigned char* ksrc = (const unsigned char*)a.k + grow + ck * 16;
             const unsigned char* vsrc = (const unsigned char*)a.v + grow + cv * 16;
-            const uint32_t dst = lds_addr0 + slot * kSlotBytes + (8 * wave + 2 * u) * 512;
+            const int first_row = 8 * wave + 2 * u;                   // wave-uniform
+            const uint32_t dst = lds_addr0 + slot * kSlotBytes + (first_row >> 5) * kUnitBytes + (first_row & 31) * 512;
             load_to_lds_16B(ksrc, dst);
-            load_to_lds_16B(vsrc, dst + kVOffset);
+            load_to_lds_16B(vsrc, dst + kUnitVOffset);
         }
     };
 
-    f32x4 acc[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY;     // running maximum of this head's scores (log2 domain), same in the 4 lanes of a head
-    float l_run = 0.f;           // this lane's share of the sum of weights
-
-    const int r0 = 32 * grp;     // this wave's half of every tile
+    WaveState st;
+    init_state(st);
 
     issue_tile(0, 0);
-    for (int it = 0; it < n_tiles; ++it) {
+    for (int it = 0; it < r.n_tiles; ++it) {
         const int slot = it & 1;
         wait_vmem_all();
         __syncthreads();
-        if (it + 1 < n_tiles) issue_tile(it + 1, slot ^ 1);
+        if (it + 1 < r.n_tiles) issue_tile(it + 1, slot ^ 1);
+        process_unit<false>(st, qf, lds_base, slot * kSlotBytes + grp * kUnitBytes,
+                            r.t0 + it * kTile + grp * kUnitTokens, r.t1, a.scale_log2e, n, g, 0, 0);
+    }
+    finish_item(st, lds_base, a, r.b, item, wq, grp, lane);
+}
 
-        const int tile_t0 = t0 + it * kTile;
-        const int kbase = slot * kSlotBytes;
-        const int vbase = kbase + kVOffset;
+template <bool PAGED>
+__global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const lds_ptr_t lds_base = (lds_ptr_t)smem;
+    const uint32_t lds_addr0 = (uint32_t)(uintptr_t)lds_base;
 
-        // ---- scores for 2 blocks of 16 tokens
-        f32x4 s[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wq = wave & 3;
+    const int grp = wave >> 2;
+    const int n = lane & 15;
+    const int g = lane >> 4;
+
+    const int item = blockIdx.x;
+    const ItemRange r = item_range(a, item);
+    if (r.t0 >= r.t1) { empty_item(a, r); return; }
+
+    bf16x8 qf[8];
+    load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
+
+    // Wave w brings rows [8w, 8w+8) of the tile's K and V codes (256 B per row, 4 rows per load);
+    // waves 0 and 1 also bring the 64 key and value scales.
+    auto issue_tile = [&](int tile, int slot) {
+        const int tile_t0 = r.t0 + tile * kTile;
+        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0);
+        const uint32_t stage = lds_addr0 + kFp8StageBase + slot * kStageBytes;
+        const int last = r.t1 - 1 - tile_t0;                          // last valid row of this tile (>= 0)
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
+        for (int j = 0; j < 2; ++j) {
+            const int row = 8 * wave + 4 * j + (lane >> 4);
+            const int in_tile = row > last ? last : row;
+            const size_t goff = (size_t)(row0 + in_tile) * 256 + (lane & 15) * 16;
+            load_to_lds_16B((const unsigned char*)a.k + goff, stage + kStageK + (8 * wave + 4 * j) * 256);
+            load_to_lds_16B((const unsigned char*)a.v + goff, stage + kStageV + (8 * wave + 4 * j) * 256);
+        }
+        if (wave < 2) {
+            const int in_tile = lane > last ? last : lane;
+            const float* src = (wave == 0 ? a.k_scale : a.v_scale) + (row0 + in_tile);
+            load_to_lds_4B(src, stage + (wave == 0 ? kStageKScale : kStageVScale));
+        }
+    };
+
+    // Convert the staged codes of one tile to the swizzled bf16 unit images (exact: every e4m3
+    // value is a bf16 value).  2048 pieces of 16 codes, 4 per thread.
+    auto convert_tile = [&](int slot) {
+        const int stage = kFp8StageBase + slot * kStageBytes;
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-                const int row = r0 + 16 * tb + n;                              // row & 15 == n
-                const int off = kbase + row * 512 + (((4 * ks + g) ^ n) << 4);
-                const bf16x8 kf = *LDS_PTR(bf16x8, off);
-                s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s[tb], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) {
+            const int piece = threadIdx.x + kAttnThreads * i;
+            const int is_v = piece >> 10;
+            const int row = (piece >> 4) & 63;
+            const int c = piece & 15;
+            const u32x4 in = *LDS_AT(u32x4, lds_base, stage + is_v * kStageV + row * 256 + c * 16);
+            bf16x8 half[2];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], false);
+                const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], true);
+                half[w >> 1][4 * (w & 1) + 0] = (__bf16)f01[0];
+                half[w >> 1][4 * (w & 1) + 1] = (__bf16)f01[1];
+                half[w >> 1][4 * (w & 1) + 2] = (__bf16)f23[0];
+                half[w >> 1][4 * (w & 1) + 3] = (__bf16)f23[1];
+            }
+            const int rr = row & 31;
+            const int key = rr & 15;
+            const int unit = (row >> 5) * kUnitBytes + rr * 512;
+            if (is_v) {
+                const int off = unit + kUnitVOffset + ((c ^ key) << 5);
+                *LDS_AT(bf16x8, lds_base, off) = half[0];
+                *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
+            } else {
+                *LDS_AT(bf16x8, lds_base, unit + (((2 * c) ^ key) << 4)) = half[0];
+                *LDS_AT(bf16x8, lds_base, unit + (((2 * c + 1) ^ key) << 4)) = half[1];
             }
         }
+    };
 
-        // ---- online softmax in the log2 domain; tokens at or past t1 are masked
-        float sv[8];
-        float m_new = m_run;
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int tok = tile_t0 + r0 + 16 * tb + 4 * g + i;
-                float x = s[tb][i] * a.scale_log2e;
-                x = tok < t1 ? x : -INFINITY;
-                sv[4 * tb + i] = x;
-                m_new = fmaxf(m_new, x);
-            }
-        }
-        m_new = fmaxf(m_new, __shfl_xor(m_new, 16));
-        m_new = fmaxf(m_new, __shfl_xor(m_new, 32));
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_safe);     // 0 when nothing was accumulated yet
-        m_run = m_new;
+    WaveState st;
+    init_state(st);
 
-        bf16x8 pf;
-        float psum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const __bf16 pb = (__bf16)fast_exp2(sv[j] - m_safe);
-            pf[j] = pb;
-            psum += (float)pb;
-        }
-        l_run = l_run * alpha + psum;
-
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-            for (int db = 0; db < 16; ++db) acc[db] *= alpha;
-        }
-
-        // ---- O^T += V^T P^T over this half tile's 32 tokens
-#pragma unroll
-        for (int db = 0; db < 16; ++db) {
-            union { bf16x8 v; s16x4 h[2]; } vf;
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-                const int row = r0 + 16 * tb + 4 * g + (n >> 2);              // row & 15 == 4g + n/4
-                const int off = vbase + row * 512 + ((db ^ (4 * g + (n >> 2))) << 5) + ((n & 3) << 3);
-                vf.h[tb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, off));
-            }
-            acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf, acc[db], 0, 0, 0);
-        }
+    issue_tile(0, 0);
+    for (int it = 0; it < r.n_tiles; ++it) {
+        const int slot = it & 1;
+        wait_vmem_all();
+        __syncthreads();          // staged tile `it` landed; everyone is done with the bf16 image of tile it-1
+        if (it + 1 < r.n_tiles) issue_tile(it + 1, slot ^ 1);
+        convert_tile(slot);
+        __syncthreads();
+        const int stage = kFp8StageBase + slot * kStageBytes;
+        process_unit<true>(st, qf, lds_base, grp * kUnitBytes, r.t0 + it * kTile + grp * kUnitTokens, r.t1,
+                           a.scale_log2e, n, g, stage + kStageKScale + grp * kUnitTokens * 4,
+                           stage + kStageVScale + grp * kUnitTokens * 4);
     }
-
-    // ---- merge the two token halves (grp 1 -> grp 0) through LDS
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    __syncthreads();                                  // every wave is done reading the ring
-    constexpr int kRegs = 66;                         // 64 accumulators + m + l
-    if (grp == 1) {
-#pragma unroll
-        for (int db = 0; db < 16; ++db)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                *LDS_PTR(float, ((wq * kRegs + db * 4 + i) * 64 + lane) * 4) = acc[db][i];
-        *LDS_PTR(float, ((wq * kRegs + 64) * 64 + lane) * 4) = m_run;
-        *LDS_PTR(float, ((wq * kRegs + 65) * 64 + lane) * 4) = l_run;
-    }
-    __syncthreads();
-    if (grp == 1) return;
-
-    {
-        const float m1 = *LDS_PTR(float, ((wq * kRegs + 64) * 64 + lane) * 4);
-        const float l1 = *LDS_PTR(float, ((wq * kRegs + 65) * 64 + lane) * 4);
-        const float m = fmaxf(m_run, m1);             // finite: this item has at least one token
-        const float w0 = fast_exp2(m_run - m);
-        const float w1 = fast_exp2(m1 - m);
-#pragma unroll
-        for (int db = 0; db < 16; ++db)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                acc[db][i] = acc[db][i] * w0 + *LDS_PTR(float, ((wq * kRegs + db * 4 + i) * 64 + lane) * 4) * w1;
-        l_run = l_run * w0 + l1 * w1;
-        m_run = m;
-    }
-
-    // ---- store: final result when the context was not split, else the partial
-    if (a.n_splits == 1) {
-        const float inv = 1.0f / l_run;
-        float* o = a.out + ((size_t)b * kHeads + head) * kHeadDim + 4 * g;
-#pragma unroll
-        for (int db = 0; db < 16; ++db) {
-            f32x4 r = acc[db] * inv;
-            *(f32x4*)(o + 16 * db) = r;
-        }
-    } else {
-        float* o = a.ws_acc + ((size_t)item * kHeads + head) * kHeadDim + 4 * g;
-#pragma unroll
-        for (int db = 0; db < 16; ++db) *(f32x4*)(o + 16 * db) = acc[db];
-        if (g == 0) {
-            float2* ml = (float2*)(a.ws_ml + ((size_t)item * kHeads + head) * 2);
-            *ml = make_float2(m_run, l_run);
-        }
-    }
+    finish_item(st, lds_base, a, r.b, item, wq, grp, lane);
 }
 
 // Merge the partial results of the splits of one sequence:
-//   out = sum_s 2^(m_s - m*) acc_s / sum_s 2^(m_s - m*) l_s,  m* = max_s m_s.
-// One thread per 4 consecutive output elements.
+//   out = sum_s 2^(m_s - m*) acc_s / sum_s 2^(m_s - m*) l_s,  m* = max_s m_s,
+// summed in split order.  One thread per 4 consecutive output elements; splits are taken four
+// at a time so that their loads are independent and in flight together.
 __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B*64*64 float4
@@ -269,23 +216,44 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
     if (b >= a.B) return;
     int L = a.seq_lens[b];
     L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
-    float4* o = (float4*)(a.out + ((size_t)b * kHeads + h) * kHeadDim) + d4;
-    if (L == 0) { *o = make_float4(0.f, 0.f, 0.f, 0.f); return; }
+    if (L == 0) return;                                               // zeros were written by the first item
     const int n_valid = (L + a.chunk_tokens - 1) / a.chunk_tokens;    // <= n_splits
     const size_t item0 = (size_t)b * a.n_splits;
+    const float2* ml_base = (const float2*)a.ws_ml + item0 * kHeads + h;
+    const float4* acc_base = (const float4*)a.ws_acc + (item0 * kHeads + h) * (kHeadDim / 4) + d4;
+
     float m = -INFINITY;
-    for (int s = 0; s < n_valid; ++s) m = fmaxf(m, a.ws_ml[((item0 + s) * kHeads + h) * 2]);
+    for (int s0 = 0; s0 < n_valid; s0 += 4) {
+        float mm[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int s = s0 + u < n_valid ? s0 + u : n_valid - 1;
+            mm[u] = ml_base[(size_t)s * kHeads].x;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) m = fmaxf(m, mm[u]);
+    }
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
     float l = 0.f;
-    for (int s = 0; s < n_valid; ++s) {
-        const float2 ml = *(const float2*)(a.ws_ml + ((item0 + s) * kHeads + h) * 2);
-        const float w = fast_exp2(ml.x - m);
-        const float4 v = *((const float4*)(a.ws_acc + ((item0 + s) * kHeads + h) * kHeadDim) + d4);
-        sum.x += w * v.x; sum.y += w * v.y; sum.z += w * v.z; sum.w += w * v.w;
-        l += w * ml.y;
+    for (int s0 = 0; s0 < n_valid; s0 += 4) {
+        float2 ml[4];
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int s = s0 + u < n_valid ? s0 + u : n_valid - 1;
+            ml[u] = ml_base[(size_t)s * kHeads];
+            v[u] = acc_base[(size_t)s * kHeads * (kHeadDim / 4)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float w = s0 + u < n_valid ? fast_exp2(ml[u].x - m) : 0.f;
+            sum.x += w * v[u].x; sum.y += w * v[u].y; sum.z += w * v[u].z; sum.w += w * v[u].w;
+            l += w * ml[u].y;
+        }
     }
     const float inv = 1.0f / l;
-    *o = make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
+    *((float4*)(a.out + ((size_t)b * kHeads + h) * kHeadDim) + d4) =
+        make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
 }
 
 // Copy the logical rows of every sequence out of a paged pool (test aid).
@@ -326,17 +294,26 @@ hipError_t prepare_decode_attn_kernels()
     e = hipFuncSetAttribute((const void*)decode_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void*)decode_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)decode_fp8_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kFp8LdsBytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)decode_fp8_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kFp8LdsBytes);
     return e;
 }
 
 hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream)
 {
-    if (kv_dtype != MFA_KV_BF16) return hipErrorNotSupported;
     const dim3 grid((unsigned)(a.B * a.n_splits));
-    if (a.block_table)
-        hipLaunchKernelGGL(decode_bf16_kernel<true>, grid, dim3(kAttnThreads), kAttnLdsBytes, stream, a);
-    else
-        hipLaunchKernelGGL(decode_bf16_kernel<false>, grid, dim3(kAttnThreads), kAttnLdsBytes, stream, a);
+    const dim3 block(kAttnThreads);
+    if (kv_dtype == MFA_KV_BF16) {
+        if (a.block_table) hipLaunchKernelGGL(decode_bf16_kernel<true>, grid, block, kAttnLdsBytes, stream, a);
+        else               hipLaunchKernelGGL(decode_bf16_kernel<false>, grid, block, kAttnLdsBytes, stream, a);
+    } else if (kv_dtype == MFA_KV_FP8_E4M3) {
+        if (a.block_table) hipLaunchKernelGGL(decode_fp8_kernel<true>, grid, block, kFp8LdsBytes, stream, a);
+        else               hipLaunchKernelGGL(decode_fp8_kernel<false>, grid, block, kFp8LdsBytes, stream, a);
+    } else {
+        return hipErrorNotSupported;
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (a.n_splits > 1) {

@@ -1,0 +1,272 @@
+// Device-side building blocks shared by the bf16 and fp8 decode attention kernels (gfx950).
+//
+// Workgroup shape common to both kernels: 8 waves; wave = 4*grp + wq.  wq selects 16 of the
+// 64 query heads, grp selects which 32-token unit of every 64-token tile the wave processes.
+// The two waves that share a SIMD (same wq, different grp) keep independent online-softmax
+// states which finish_item() merges through LDS, so one wave's MFMA work can overlap the
+// other's softmax.
+//
+// LDS image of one 32-token unit (what process_unit reads), bf16:
+//   K rows 0..31 then V rows 0..31, 512 B per row (256 bf16).
+//   K row r stores its 16-byte chunk c at position c ^ (r & 15);
+//   V row r stores its 32-byte chunk c at position c ^ (r & 15).
+// With these swizzles the 16-row x 16-byte MFMA operand reads of K and the 16-row x 32-byte
+// transposing reads of V each touch every LDS bank exactly once.
+//
+// MFMA shapes (v_mfma_f32_16x16x32_bf16; lane = 16*g + n):
+//   scores   S^T[token, head] = K[token, :] . Q[head, :]^T     A = K rows, B = Q
+//            lane holds S^T[token 4g+i, head n], i = 0..3, for each 16-token block
+//   output   O^T[d, head] += V^T[d, token] . P^T[token, head]  A = V^T, B = P
+//            lane holds O^T[d = 16*db + 4g + i, head n]
+// The score block a lane ends up with is exactly the B-operand slice it must supply for the
+// second product (8 tokens of its own head), so attention weights never move between lanes and
+// the per-head statistics live in the lanes of that head.
+#pragma once
+#include "mfa_internal.hpp"
+
+namespace mfa {
+
+typedef __attribute__((address_space(3))) unsigned char* lds_ptr_t;
+#define LDS_AT(T, base, byte_off) ((__attribute__((address_space(3))) T*)((base) + (byte_off)))
+
+constexpr int kUnitTokens = 32;
+constexpr int kUnitBytes = 32768;        // K 32x512 B then V 32x512 B
+constexpr int kUnitVOffset = 16384;
+constexpr int kAttnThreads = 512;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// s_waitcnt that constrains only the vector-memory counter: vmcnt(0).
+__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// Direct global->LDS loads: `bytes` per lane land at lds_addr + bytes*lane (lds_addr is
+// wave-uniform and travels in M0).  Issued as inline assembly so that the compiler does not
+// make later LDS reads of *other* buffers wait for them; completion is awaited explicitly
+// with wait_vmem_all() followed by a workgroup barrier.  M0 is not otherwise live in these
+// kernels.  The s_nop covers the wait state required between writing M0 and an LDS-direct load.
+__device__ __forceinline__ void load_to_lds_16B(const void* gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gptr), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void load_to_lds_4B(const void* gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :: "v"(gptr), "s"(lds_addr) : "memory");
+}
+
+// max over the four lanes {n, n+16, n+32, n+48} that hold one head, without touching LDS:
+// v_permlane32_swap exchanges the upper half of the first operand with the lower half of the
+// second, v_permlane16_swap exchanges odd 16-lane rows of the first with even rows of the second.
+__device__ __forceinline__ float head_max(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const unsigned v = __float_as_uint(x);
+    const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float head_sum(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const unsigned v = __float_as_uint(x);
+    const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// Running state of one wave: 16 heads x 256 output dims, spread as described above.
+struct WaveState {
+    f32x4 acc[16];
+    float m;     // running maximum of this head's scores in the log2 domain (equal in the 4 lanes of a head)
+    float l;     // this lane's share of the sum of weights
+};
+
+__device__ __forceinline__ void init_state(WaveState& st)
+{
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    st.m = -INFINITY;
+    st.l = 0.f;
+}
+
+// Query fragments of this lane: B operand of the score product, d = 32*ks + 8*g + j.
+__device__ __forceinline__ void load_q_fragments(bf16x8 (&qf)[8], const void* q, int b, int head, int g)
+{
+    const bf16x8* qp = (const bf16x8*)((const uint16_t*)q + ((size_t)b * kHeads + head) * kHeadDim + 8 * g);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = qp[ks * 4];
+}
+
+// One 32-token unit: scores, online softmax, weighted sum.
+//   unit_base  LDS byte offset of the unit image
+//   unit_t0    index (within the sequence) of the unit's first token; tokens >= t1 are masked
+//   FP8        the image holds unscaled codes converted to bf16; kscale/vscale point (LDS byte
+//              offsets) at the fp32 per-token scales of the unit's 32 tokens
+template <bool FP8>
+__device__ __forceinline__ void process_unit(WaveState& st, const bf16x8 (&qf)[8], lds_ptr_t lds_base, int unit_base,
+                                             int unit_t0, int t1, float scale_log2e, int n, int g, int kscale_off,
+                                             int vscale_off)
+{
+    const int kbase = unit_base;
+    const int vbase = unit_base + kUnitVOffset;
+    const int k_lane_off = n * 512;                     // K: row n of a 16-token block, swizzle key n
+    const int v_row = 4 * g + (n >> 2);                 // V: row within a 16-token block = swizzle key
+    const int v_lane_off = v_row * 512 + ((n & 3) << 3);
+
+    // ---- scores for 2 blocks of 16 tokens
+    f32x4 s[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const int off = kbase + tb * 8192 + k_lane_off + (((4 * ks + g) ^ n) << 4);
+            const bf16x8 kf = *LDS_AT(bf16x8, lds_base, off);
+            s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s[tb], 0, 0, 0);
+        }
+    }
+    f32x4 vsc[2];
+    if (FP8) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const f32x4 ksc = *LDS_AT(f32x4, lds_base, kscale_off + (16 * tb + 4 * g) * 4);
+            vsc[tb] = *LDS_AT(f32x4, lds_base, vscale_off + (16 * tb + 4 * g) * 4);
+            s[tb] *= ksc;
+        }
+    }
+
+    // ---- online softmax in the log2 domain; tokens at or past t1 are masked
+    float sv[8];
+    float m_new = st.m;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tok = unit_t0 + 16 * tb + 4 * g + i;
+            float x = s[tb][i] * scale_log2e;
+            x = tok < t1 ? x : -INFINITY;
+            sv[4 * tb + i] = x;
+            m_new = fmaxf(m_new, x);
+        }
+    }
+    m_new = head_max(m_new);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2(st.m - m_safe);      // 0 while nothing has been accumulated
+    st.m = m_new;
+
+    bf16x8 pf;
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float p = fast_exp2(sv[j] - m_safe);
+        if (FP8) {
+            // the value scale rides on the weight; the normaliser sums the unscaled weight
+            pf[j] = (__bf16)(p * vsc[j >> 2][j & 3]);
+            psum += p;
+        } else {
+            // normalise by the sum of the rounded weights actually multiplied into V
+            const __bf16 pb = (__bf16)p;
+            pf[j] = pb;
+            psum += (float)pb;
+        }
+    }
+    st.l = st.l * alpha + psum;
+
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int db = 0; db < 16; ++db) st.acc[db] *= alpha;
+    }
+
+    // ---- O^T += V^T P^T over the unit's 32 tokens
+#pragma unroll
+    for (int db = 0; db < 16; ++db) {
+        union { bf16x8 v; s16x4 h[2]; } vf;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const int off = vbase + tb * 8192 + v_lane_off + ((db ^ v_row) << 5);
+            vf.h[tb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
+        }
+        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf, st.acc[db], 0, 0, 0);
+    }
+}
+
+// After the last tile: merge the two token halves (grp 1 -> grp 0) through LDS (the tile buffers
+// are dead by then; the caller guarantees no direct load is in flight), then grp 0 stores either
+// the final result (one split) or the unnormalised partial (acc, m, l) of this work item.
+__device__ __forceinline__ void finish_item(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, int b, int item,
+                                            int wq, int grp, int lane)
+{
+    const int n = lane & 15, g = lane >> 4;
+    const int head = 16 * wq + n;
+    st.l = head_sum(st.l);
+    __syncthreads();                                  // every wave is done reading the tile buffers
+    constexpr int kRegs = 66;                         // 64 accumulators + m + l
+    if (grp == 1) {
+#pragma unroll
+        for (int db = 0; db < 16; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *LDS_AT(float, lds_base, ((wq * kRegs + db * 4 + i) * 64 + lane) * 4) = st.acc[db][i];
+        *LDS_AT(float, lds_base, ((wq * kRegs + 64) * 64 + lane) * 4) = st.m;
+        *LDS_AT(float, lds_base, ((wq * kRegs + 65) * 64 + lane) * 4) = st.l;
+    }
+    __syncthreads();
+    if (grp == 1) return;
+
+    const float m1 = *LDS_AT(float, lds_base, ((wq * kRegs + 64) * 64 + lane) * 4);
+    const float l1 = *LDS_AT(float, lds_base, ((wq * kRegs + 65) * 64 + lane) * 4);
+    const float m = fmaxf(st.m, m1);                  // finite: the item has at least one token, seen by grp 0
+    const float w0 = fast_exp2(st.m - m);
+    const float w1 = fast_exp2(m1 - m);
+#pragma unroll
+    for (int db = 0; db < 16; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            st.acc[db][i] = st.acc[db][i] * w0 + *LDS_AT(float, lds_base, ((wq * kRegs + db * 4 + i) * 64 + lane) * 4) * w1;
+    const float l = st.l * w0 + l1 * w1;
+
+    if (a.n_splits == 1) {
+        const float inv = 1.0f / l;
+        float* o = a.out + ((size_t)b * kHeads + head) * kHeadDim + 4 * g;
+#pragma unroll
+        for (int db = 0; db < 16; ++db) {
+            const f32x4 r = st.acc[db] * inv;
+            *(f32x4*)(o + 16 * db) = r;
+        }
+    } else {
+        float* o = a.ws_acc + ((size_t)item * kHeads + head) * kHeadDim + 4 * g;
+#pragma unroll
+        for (int db = 0; db < 16; ++db) *(f32x4*)(o + 16 * db) = st.acc[db];
+        if (g == 0) *(float2*)(a.ws_ml + ((size_t)item * kHeads + head) * 2) = make_float2(m, l);
+    }
+}
+
+// Work item bookkeeping common to both kernels.
+struct ItemRange {
+    int b, split, t0, t1, n_tiles;
+};
+__device__ __forceinline__ ItemRange item_range(const AttnArgs& a, int item)
+{
+    ItemRange r;
+    r.b = item / a.n_splits;
+    r.split = item - r.b * a.n_splits;
+    int L = a.seq_lens[r.b];
+    L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
+    r.t0 = r.split * a.chunk_tokens;
+    r.t1 = (r.t0 + a.chunk_tokens < L) ? r.t0 + a.chunk_tokens : L;
+    r.n_tiles = (r.t1 - r.t0 + kTile - 1) / kTile;
+    return r;
+}
+
+// An item without tokens: the first item of an empty sequence writes the zero result.
+__device__ __forceinline__ void empty_item(const AttnArgs& a, const ItemRange& r)
+{
+    if (r.split == 0) {
+        float4* o = (float4*)(a.out + (size_t)r.b * kHeads * kHeadDim);
+        for (int i = threadIdx.x; i < kHeads * kHeadDim / 4; i += kAttnThreads) o[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+}  // namespace mfa

@@ -15,6 +15,7 @@ constexpr int kTile = 64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // How the context of one call is cut into work items.  Pure host arithmetic.
 struct SplitPlan {

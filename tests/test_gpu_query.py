@@ -1,0 +1,65 @@
+"""GPU parity for the low-rank query path (x.W_qa -> RMSNorm -> .W_qb) and for the fused decode step
+of the fifth named workload (query path feeding attention over an fp8 cache)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_19427_amd as mfa
+from paper_2507_19427_amd import workloads as W
+from oracle import mfa_oracle as O
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+TOL_Q = 1e-2     # row-normalised, bf16 output; c_hat is rounded to bf16 before the second product
+
+
+def _gpu_q(ctx, c):
+    q = mfa.mfa_query_proj(ctx, c.x.cuda(), c.w_qa.cuda(), c.w_qb.cuda(),
+                           rms_gain=None if c.gain is None else c.gain.cuda())
+    torch.cuda.synchronize()
+    return q.cpu()
+
+
+def _oracle_q(c):
+    b = O.bits_of
+    return O.query_proj(b(c.x), b(c.w_qa), b(c.w_qb), c.eps, gain=None if c.gain is None else c.gain.numpy(),
+                        want_f64=True)
+
+
+@pytest.mark.parametrize("B,d_model,r,gain", [(5, 256, 128, False), (130, 448, 256, True), (128, 1024, 384, True)])
+def test_query_path_small(B, d_model, r, gain):
+    print(f"\n[case] query path B={B} d_model={d_model} r={r} gain={gain}", flush=True)
+    ctx = U.get_ctx(max_batch=256, max_seq_len=1024, d_model=d_model, q_rank=r)
+    c = W.make_query_proj_case("q", 300 + B, B=B, d_model=d_model, r=r, w_std=0.05, with_gain=gain)
+    got = _gpu_q(ctx, c)
+    assert got.shape == (B, 64, 256) and got.dtype == torch.bfloat16
+    _, q64, _ = _oracle_q(c)
+    err = U.row_normalised_error(got.float().numpy().reshape(B, -1), q64)
+    print(f"   row-normalised max error {err:.3e}", flush=True)
+    assert err <= TOL_Q
+
+
+def test_config5_query_path_and_fp8_attention():
+    print("\n[case] cfg5 query path + fp8 attention, B=128 ctx=8192", flush=True)
+    ctx = U.get_ctx()
+    c = W.config5_query()
+    q_gpu = _gpu_q(ctx, c)
+    q16, q64, _ = _oracle_q(c)
+    err_q = U.row_normalised_error(q_gpu.float().numpy().reshape(128, -1), q64)
+    print(f"   query path row-normalised max error {err_q:.3e}", flush=True)
+    assert err_q <= TOL_Q
+
+    case = W.config5_fp8_cache(q_gpu, poison=False)
+    got = U.run_gpu(ctx, case)
+    assert np.isfinite(got).all()
+    rows = U.sample_rows(case, 24)
+    sub = np.stack([got[b, h] for b, h in rows])
+    # staged: oracle attention on the very query bits the GPU produced
+    err_staged = U.row_normalised_error(sub, U.run_oracle(case, rows=rows))
+    # end to end: oracle attention on the oracle's own (fp64 chain, rounded once) query
+    case.q = torch.from_numpy(q16.view(np.int16).reshape(128, 64, 256)).view(torch.bfloat16)
+    err_e2e = U.row_normalised_error(sub, U.run_oracle(case, rows=rows))
+    print(f"   attention staged error {err_staged:.3e}, end-to-end error {err_e2e:.3e}", flush=True)
+    assert err_staged <= U.TOL_FP8 and err_e2e <= U.TOL_FP8
