@@ -170,6 +170,16 @@ MFA_API mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_
                                   const int32_t* seq_lens, int32_t max_seq_len_hint, int32_t B,
                                   void* dst, int64_t dst_seq_stride_tokens, void* hip_stream);
 
+/*
+ * Measurement aid, not part of the serving path: while both handles are non-NULL
+ * (hipEvent_t passed as void*, created by the caller with timing enabled), every
+ * mfa_decode_attn / mfa_decode_attn_paged call on this context records
+ * `ev_before` on the call's stream immediately before its streaming kernel (the
+ * one that reads the cache) and `ev_after` immediately after it, so the caller
+ * can time that kernel alone with hipEventElapsedTime.  Pass NULLs to stop.
+ */
+MFA_API mfa_status mfa_debug_set_kernel_events(mfa_ctx* ctx, void* ev_before, void* ev_after);
+
 /* Number of context splits the next mfa_decode_attn* call with these host
  * arguments would use (each split's partial result is merged by the library).
  * Pure host function; 0 on invalid arguments. */

@@ -25,7 +25,7 @@ MFA_KV_FP8_E4M3 = 1
 EXPORTS = [
     "mfa_decode_workspace_bytes", "mfa_decode_init", "mfa_decode_destroy", "mfa_status_string",
     "mfa_query_proj", "mfa_decode_attn", "mfa_decode_attn_paged", "mfa_debug_gather_paged",
-    "mfa_decode_num_splits",
+    "mfa_decode_num_splits", "mfa_debug_set_kernel_events",
 ]
 
 
@@ -90,6 +90,8 @@ def lib():
     L.mfa_decode_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, i32, vp, i32, i32, vp, vp]
     L.mfa_debug_gather_paged.restype = ctypes.c_int
     L.mfa_debug_gather_paged.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, i64, vp]
+    L.mfa_debug_set_kernel_events.restype = ctypes.c_int
+    L.mfa_debug_set_kernel_events.argtypes = [vp, vp, vp]
     L.mfa_decode_num_splits.restype = i32
     L.mfa_decode_num_splits.argtypes = [vp, i32, i32]
     _lib = L
@@ -261,3 +263,31 @@ def mfa_debug_gather_paged(ctx: MfaContext, pool, block_table, seq_lens, max_seq
                                         block_table.shape[1], _ptr(seq_lens), int(max_seq_len_hint), B, _ptr(dst),
                                         dst.shape[1], _stream()), "mfa_debug_gather_paged")
     return dst
+
+
+def mfa_debug_set_kernel_events(ctx: MfaContext, ev_before=None, ev_after=None):
+    """Record the two torch.cuda.Event objects (timing enabled, already recorded once so that their
+    HIP handles exist) around the streaming kernel of every later attention call; None, None stops."""
+    hb = None if ev_before is None else ctypes.c_void_p(ev_before.cuda_event)
+    ha = None if ev_after is None else ctypes.c_void_p(ev_after.cuda_event)
+    _check(lib().mfa_debug_set_kernel_events(ctx.handle, hb, ha), "mfa_debug_set_kernel_events")
+
+
+class PreparedDecodeAttn:
+    """mfa_decode_attn with its arguments marshalled once: calling the object only crosses the C
+    boundary (for loops that must not pay Python-side checks per step).  The tensors are kept alive."""
+
+    def __init__(self, ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_hint, out, k_scale=None,
+                 v_scale=None):
+        mfa_decode_attn(ctx, q, k_cache, v_cache, seq_lens, max_seq_len_hint, k_scale=k_scale, v_scale=v_scale,
+                        out=out)                       # validates shapes and types once
+        self._keep = (ctx, q, k_cache, v_cache, seq_lens, out, k_scale, v_scale)
+        self._fn = lib().mfa_decode_attn
+        self._args = (ctx.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
+                      _kv_dtype(k_cache), k_cache.shape[1], _ptr(seq_lens), int(max_seq_len_hint), q.shape[0],
+                      _ptr(out), _stream())
+
+    def __call__(self):
+        st = self._fn(*self._args)
+        if st != MFA_OK:
+            raise MfaError(st, "mfa_decode_attn")

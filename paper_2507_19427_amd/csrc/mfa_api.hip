@@ -18,6 +18,8 @@ struct mfa_ctx {
     void* ws_chat;
     int32_t qproj_split_k;
     int32_t qproj_rows_pad;
+    hipEvent_t ev_before;      // measurement aid: recorded around the streaming kernel when both are set
+    hipEvent_t ev_after;
 };
 
 namespace {
@@ -164,6 +166,8 @@ mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t work
     ctx->ws_chat = base + w.chat;
     ctx->qproj_split_k = w.split_k;
     ctx->qproj_rows_pad = w.rows_pad;
+    ctx->ev_before = nullptr;
+    ctx->ev_after = nullptr;
     *out_ctx = ctx;
     return MFA_OK;
 }
@@ -180,6 +184,15 @@ const char* mfa_status_string(mfa_status s)
         case MFA_ERR_HIP: return "HIP runtime error";
     }
     return "unknown status";
+}
+
+mfa_status mfa_debug_set_kernel_events(mfa_ctx* ctx, void* ev_before, void* ev_after)
+{
+    if (!ctx) return MFA_ERR_INVALID_ARG;
+    if ((ev_before == nullptr) != (ev_after == nullptr)) return MFA_ERR_INVALID_ARG;
+    ctx->ev_before = static_cast<hipEvent_t>(ev_before);
+    ctx->ev_after = static_cast<hipEvent_t>(ev_after);
+    return MFA_OK;
 }
 
 int32_t mfa_decode_num_splits(const mfa_ctx* ctx, int32_t B, int32_t max_seq_len_hint)
@@ -221,7 +234,7 @@ mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_cache, con
     a.seq_lens = seq_lens; a.block_table = nullptr; a.out = out;
     a.seq_stride_tokens = kv_seq_stride_tokens; a.max_blocks_per_seq = 0;
     fill_common(ctx, a, B, max_seq_len_hint);
-    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream), ctx->ev_before, ctx->ev_after);
     if (e == hipErrorNotSupported) return MFA_ERR_UNSUPPORTED;
     return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }
@@ -242,7 +255,7 @@ mfa_status mfa_decode_attn_paged(mfa_ctx* ctx, const void* q, const void* k_pool
     a.seq_lens = seq_lens; a.block_table = block_table; a.out = out;
     a.seq_stride_tokens = 0; a.max_blocks_per_seq = max_blocks_per_seq;
     fill_common(ctx, a, B, max_seq_len_hint);
-    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream), ctx->ev_before, ctx->ev_after);
     if (e == hipErrorNotSupported) return MFA_ERR_UNSUPPORTED;
     return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }

@@ -205,22 +205,26 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
 
 // Merge the partial results of the splits of one sequence:
 //   out = sum_s 2^(m_s - m*) acc_s / sum_s 2^(m_s - m*) l_s,  m* = max_s m_s,
-// summed in split order.  One thread per 4 consecutive output elements; splits are taken four
-// at a time so that their loads are independent and in flight together.
+// summed in split order.  One thread per float4 of the partial's lane-order layout; splits are
+// taken four at a time so that their loads are independent and in flight together.
 __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B*64*64 float4
-    const int d4 = (int)(idx & 63);
-    const int h = (int)((idx >> 6) & 63);
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B * 4096 float4
+    const int p = (int)(idx & 4095);                                  // position in the partial's lane-order layout
     const int b = (int)(idx >> 12);
     if (b >= a.B) return;
+    const int lane = p & 63;
+    const int db = (p >> 6) & 15;
+    const int wq = p >> 10;
+    const int h = 16 * wq + (lane & 15);
+    const int d = 16 * db + 4 * (lane >> 4);
     int L = a.seq_lens[b];
     L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
     if (L == 0) return;                                               // zeros were written by the first item
     const int n_valid = (L + a.chunk_tokens - 1) / a.chunk_tokens;    // <= n_splits
     const size_t item0 = (size_t)b * a.n_splits;
     const float2* ml_base = (const float2*)a.ws_ml + item0 * kHeads + h;
-    const float4* acc_base = (const float4*)a.ws_acc + (item0 * kHeads + h) * (kHeadDim / 4) + d4;
+    const float4* acc_base = (const float4*)a.ws_acc + item0 * (kHeads * kHeadDim / 4) + p;
 
     float m = -INFINITY;
     for (int s0 = 0; s0 < n_valid; s0 += 4) {
@@ -242,7 +246,7 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u < n_valid ? s0 + u : n_valid - 1;
             ml[u] = ml_base[(size_t)s * kHeads];
-            v[u] = acc_base[(size_t)s * kHeads * (kHeadDim / 4)];
+            v[u] = acc_base[(size_t)s * (kHeads * kHeadDim / 4)];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -252,7 +256,7 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
         }
     }
     const float inv = 1.0f / l;
-    *((float4*)(a.out + ((size_t)b * kHeads + h) * kHeadDim) + d4) =
+    *(float4*)(a.out + ((size_t)b * kHeads + h) * kHeadDim + d) =
         make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
 }
 
@@ -301,21 +305,23 @@ hipError_t prepare_decode_attn_kernels()
     return e;
 }
 
-hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream)
+hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream,
+                              hipEvent_t ev_before, hipEvent_t ev_after)
 {
     const dim3 grid((unsigned)(a.B * a.n_splits));
     const dim3 block(kAttnThreads);
+    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return hipErrorNotSupported;
+    if (ev_before && ev_after && hipEventRecord(ev_before, stream) != hipSuccess) return hipErrorInvalidValue;
     if (kv_dtype == MFA_KV_BF16) {
         if (a.block_table) hipLaunchKernelGGL(decode_bf16_kernel<true>, grid, block, kAttnLdsBytes, stream, a);
         else               hipLaunchKernelGGL(decode_bf16_kernel<false>, grid, block, kAttnLdsBytes, stream, a);
-    } else if (kv_dtype == MFA_KV_FP8_E4M3) {
+    } else {
         if (a.block_table) hipLaunchKernelGGL(decode_fp8_kernel<true>, grid, block, kFp8LdsBytes, stream, a);
         else               hipLaunchKernelGGL(decode_fp8_kernel<false>, grid, block, kFp8LdsBytes, stream, a);
-    } else {
-        return hipErrorNotSupported;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (ev_before && ev_after && hipEventRecord(ev_after, stream) != hipSuccess) return hipErrorInvalidValue;
     if (a.n_splits > 1) {
         const unsigned blocks = (unsigned)(((size_t)a.B * kHeads * (kHeadDim / 4) + 255) / 256);
         hipLaunchKernelGGL(merge_splits_kernel, dim3(blocks), dim3(256), 0, stream, a);

@@ -192,55 +192,54 @@ __device__ __forceinline__ void process_unit(WaveState& st, const bf16x8 (&qf)[8
     }
 }
 
-// After the last tile: merge the two token halves (grp 1 -> grp 0) through LDS (the tile buffers
-// are dead by then; the caller guarantees no direct load is in flight), then grp 0 stores either
-// the final result (one split) or the unnormalised partial (acc, m, l) of this work item.
-__device__ __forceinline__ void finish_item(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, int b, int item,
+// After the last tile the two waves that share 16 heads (grp 0 and 1: the two token halves of
+// every tile) exchange halves of their accumulators through LDS (the tile buffers are dead by
+// then; the caller guarantees no direct load is in flight): grp 0 finishes output blocks 0..7,
+// grp 1 blocks 8..15, so all eight waves merge and store in parallel.  One split: the final
+// result goes to `out`.  Several splits: the unnormalised partial goes to the workspace in
+// lane order (float4 index (wq*16 + db)*64 + lane, fully coalesced), with (m, l) per head.
+template <int KEEP, int SEND>
+__device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, int b, int item,
                                             int wq, int grp, int lane)
 {
     const int n = lane & 15, g = lane >> 4;
     const int head = 16 * wq + n;
+    const int mine = (wq * 2 + grp) * 8;              // my 8 KB exchange slots (1 KB each)
+    const int theirs = (wq * 2 + (grp ^ 1)) * 8;
+    constexpr int kMlOff = 65536;                     // (m, l) exchange area after the 64 KB of blocks
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *LDS_AT(f32x4, lds_base, (mine + i) * 1024 + lane * 16) = st.acc[SEND + i];
+    *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + grp) * 2 + 0) * 256 + lane * 4) = st.m;
+    *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + grp) * 2 + 1) * 256 + lane * 4) = st.l;
+    __syncthreads();
+    const float m_o = *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + (grp ^ 1)) * 2 + 0) * 256 + lane * 4);
+    const float l_o = *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + (grp ^ 1)) * 2 + 1) * 256 + lane * 4);
+    const float m = fmaxf(st.m, m_o);                 // finite: the item has a token, seen by grp 0
+    const float w_s = fast_exp2(st.m - m);
+    const float w_o = fast_exp2(m_o - m);
+    const float l = st.l * w_s + l_o * w_o;
+    const float inv = 1.0f / l;
+    const bool final_result = a.n_splits == 1;
+    float* o = a.out + ((size_t)b * kHeads + head) * kHeadDim + 4 * g;
+    f32x4* part = (f32x4*)a.ws_acc + (size_t)item * (kHeads * kHeadDim / 4) + (size_t)wq * 16 * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const f32x4 other = *LDS_AT(f32x4, lds_base, (theirs + i) * 1024 + lane * 16);
+        const f32x4 r = st.acc[KEEP + i] * w_s + other * w_o;
+        if (final_result) *(f32x4*)(o + 16 * (KEEP + i)) = r * inv;
+        else part[(KEEP + i) * 64] = r;
+    }
+    if (!final_result && grp == 0 && g == 0)
+        *(float2*)(a.ws_ml + ((size_t)item * kHeads + head) * 2) = make_float2(m, l);
+}
+
+__device__ __forceinline__ void finish_item(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, int b, int item,
+                                            int wq, int grp, int lane)
+{
     st.l = head_sum(st.l);
     __syncthreads();                                  // every wave is done reading the tile buffers
-    constexpr int kRegs = 66;                         // 64 accumulators + m + l
-    if (grp == 1) {
-#pragma unroll
-        for (int db = 0; db < 16; ++db)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                *LDS_AT(float, lds_base, ((wq * kRegs + db * 4 + i) * 64 + lane) * 4) = st.acc[db][i];
-        *LDS_AT(float, lds_base, ((wq * kRegs + 64) * 64 + lane) * 4) = st.m;
-        *LDS_AT(float, lds_base, ((wq * kRegs + 65) * 64 + lane) * 4) = st.l;
-    }
-    __syncthreads();
-    if (grp == 1) return;
-
-    const float m1 = *LDS_AT(float, lds_base, ((wq * kRegs + 64) * 64 + lane) * 4);
-    const float l1 = *LDS_AT(float, lds_base, ((wq * kRegs + 65) * 64 + lane) * 4);
-    const float m = fmaxf(st.m, m1);                  // finite: the item has at least one token, seen by grp 0
-    const float w0 = fast_exp2(st.m - m);
-    const float w1 = fast_exp2(m1 - m);
-#pragma unroll
-    for (int db = 0; db < 16; ++db)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            st.acc[db][i] = st.acc[db][i] * w0 + *LDS_AT(float, lds_base, ((wq * kRegs + db * 4 + i) * 64 + lane) * 4) * w1;
-    const float l = st.l * w0 + l1 * w1;
-
-    if (a.n_splits == 1) {
-        const float inv = 1.0f / l;
-        float* o = a.out + ((size_t)b * kHeads + head) * kHeadDim + 4 * g;
-#pragma unroll
-        for (int db = 0; db < 16; ++db) {
-            const f32x4 r = st.acc[db] * inv;
-            *(f32x4*)(o + 16 * db) = r;
-        }
-    } else {
-        float* o = a.ws_acc + ((size_t)item * kHeads + head) * kHeadDim + 4 * g;
-#pragma unroll
-        for (int db = 0; db < 16; ++db) *(f32x4*)(o + 16 * db) = st.acc[db];
-        if (g == 0) *(float2*)(a.ws_ml + ((size_t)item * kHeads + head) * 2) = make_float2(m, l);
-    }
+    if (grp == 0) finish_half<0, 8>(st, lds_base, a, b, item, wq, grp, lane);
+    else          finish_half<8, 0>(st, lds_base, a, b, item, wq, grp, lane);
 }
 
 // Work item bookkeeping common to both kernels.

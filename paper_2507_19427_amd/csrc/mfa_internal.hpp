@@ -50,7 +50,8 @@ struct AttnArgs {
 };
 
 // Launchers (enqueue only; return the launch status).
-hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream);
+hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream,
+                              hipEvent_t ev_before, hipEvent_t ev_after);   // events may be NULL
 hipError_t prepare_decode_attn_kernels();   // one-time function attributes (dynamic LDS size)
 
 struct QProjArgs {
