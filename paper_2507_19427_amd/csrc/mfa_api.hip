@@ -16,7 +16,7 @@ struct mfa_ctx {
     float* ws_ml;
     float* ws_c;
     void* ws_chat;
-    int32_t qproj_split_k;
+    QProjPlan qproj;
     int32_t qproj_rows_pad;
     hipEvent_t ev_before;      // measurement aid: recorded around the streaming kernel when both are set
     hipEvent_t ev_after;
@@ -70,19 +70,20 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Carve {
     size_t acc, ml, c, chat, total;
     size_t max_items;
-    int32_t split_k, rows_pad;
+    QProjPlan qproj;
+    int32_t rows_pad;
 };
 
 Carve carve(const mfa_config* c, int32_t target)
 {
     Carve w;
     w.max_items = max_items_for(c, target);
-    w.split_k = qproj_split_k(c->d_model);
+    w.qproj = plan_qproj(c->d_model, c->q_rank);
     w.rows_pad = (c->max_batch + kQProjRows - 1) / kQProjRows * kQProjRows;
     size_t off = 0;
     w.acc = off; off = align_up(off + w.max_items * kPartialAccFloats * sizeof(float), 256);
     w.ml = off;  off = align_up(off + w.max_items * kPartialMlFloats * sizeof(float), 256);
-    w.c = off;   off = align_up(off + (size_t)w.split_k * w.rows_pad * c->q_rank * sizeof(float), 256);
+    w.c = off;   off = align_up(off + (size_t)w.qproj.split_k * w.rows_pad * c->q_rank * sizeof(float), 256);
     w.chat = off; off = align_up(off + (size_t)w.rows_pad * c->q_rank * 2, 256);
     w.total = off;
     return w;
@@ -150,7 +151,8 @@ mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t work
     int prev = -1;
     if (hipGetDevice(&prev) != hipSuccess) return MFA_ERR_HIP;
     if (prev != cfg->device && hipSetDevice(cfg->device) != hipSuccess) return MFA_ERR_HIP;
-    const hipError_t e = prepare_decode_attn_kernels();
+    hipError_t e = prepare_decode_attn_kernels();
+    if (e == hipSuccess) e = prepare_query_proj_kernels();
     if (prev != cfg->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) return MFA_ERR_HIP;
 
@@ -164,7 +166,7 @@ mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t work
     ctx->ws_ml = reinterpret_cast<float*>(base + w.ml);
     ctx->ws_c = reinterpret_cast<float*>(base + w.c);
     ctx->ws_chat = base + w.chat;
-    ctx->qproj_split_k = w.split_k;
+    ctx->qproj = w.qproj;
     ctx->qproj_rows_pad = w.rows_pad;
     ctx->ev_before = nullptr;
     ctx->ev_after = nullptr;
@@ -215,7 +217,8 @@ mfa_status mfa_query_proj(mfa_ctx* ctx, const void* x, const void* w_qa, const f
     a.ws_c = ctx->ws_c; a.ws_chat = ctx->ws_chat;
     a.B = B; a.d_model = ctx->cfg.d_model; a.q_rank = ctx->cfg.q_rank;
     a.n_out = ctx->cfg.n_q_heads * ctx->cfg.head_dim;
-    a.split_k = ctx->qproj_split_k;
+    a.split_k = ctx->qproj.split_k;
+    a.k_per_split = ctx->qproj.k_per_split;
     a.eps = ctx->cfg.rms_eps;
     return launch_query_proj(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }

@@ -64,10 +64,16 @@ struct QProjArgs {
     void* ws_chat;        // bf16 [B_pad][q_rank]
     int32_t B, d_model, q_rank, n_out;
     int32_t split_k;
+    int32_t k_per_split;  // multiple of 32
     float eps;
 };
-constexpr int kQProjRows = 128;   // rows of x one workgroup column covers
-int32_t qproj_split_k(int32_t d_model);
+constexpr int kQProjRows = 128;   // rows of x one workgroup covers
+struct QProjPlan {
+    int32_t split_k;      // K splits of the first product (fp32 partials in the workspace)
+    int32_t k_per_split;
+};
+QProjPlan plan_qproj(int32_t d_model, int32_t q_rank);
+hipError_t prepare_query_proj_kernels();   // one-time function attributes (dynamic LDS size)
 hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream);
 
 hipError_t launch_gather_paged(const void* pool, int32_t row_bytes, const int32_t* block_table,

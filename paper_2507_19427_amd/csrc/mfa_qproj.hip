@@ -3,147 +3,274 @@
 //   1. split-K bf16 MFMA GEMM, fp32 partial sums of c into the workspace;
 //   2. reduce the partials, normalise, apply the gain, round to bf16;
 //   3. bf16 MFMA GEMM writing q in bf16.
-// With at most a few hundred rows of x both products are bound by streaming the
-// weights once; every workgroup covers all (up to 128) rows of x so each weight is
-// read from HBM exactly once.
-#include "mfa_internal.hpp"
+// With at most a few hundred rows of x both products are bound by streaming the weights
+// once, so the GEMM is built like the attention kernel's value product: a workgroup owns a
+// strip of 128 output columns and all (up to 128) rows of x, streams its [K, 128] slice of
+// W through LDS with global->LDS direct loads (256 B per row, two stages of 256 rows), and
+// feeds v_mfma_f32_16x16x32_bf16 with
+//   A = W^T  (16 columns x 32 k) read with the LDS transposing read,
+//   B = x^T  (32 k x 16 rows)    loaded from global memory (L2-resident) one stage ahead,
+// giving C^T[column, row]; a lane ends up with 4 consecutive columns of one row.  The eight
+// waves are 4 row groups x 2 interleaved halves of the k steps, so every x element is fetched
+// by one wave only; the two halves are added through LDS at the end.
+#include "mfa_attn_core.hpp"
 
 namespace mfa {
 
 namespace {
 
-constexpr int kTileN = 64;       // output columns per workgroup
-constexpr int kStepK = 32;       // one MFMA K step
-constexpr int kLdsRow = 80;      // bytes per LDS row: 32 bf16 + 16 B pad (odd multiple of 16 B -> no bank clash)
+constexpr int kStripN = 128;                 // output columns per workgroup
+constexpr int kRowBytes = kStripN * 2;       // 256 B of W per k row
+constexpr int kStageRows = 256;              // k rows per stage
+constexpr int kStageBytes = kStageRows * kRowBytes;   // 64 KB
+constexpr int kGemmLdsBytes = 2 * kStageBytes;
+constexpr int kGemmThreads = 512;
+constexpr int kStepsPerStage = kStageRows / 32;
+
+// Swizzle key of a W row in LDS: its 32-byte chunk c is stored at position c ^ key.  The 16 rows
+// touched by one transposing read (rows 8g + 4t + i, g = 0..3, i = 0..3) get keys 2g + i/2, so the
+// 16 x 32 B of the read spread over all eight 32-byte positions of the 256-byte row.
+__device__ __forceinline__ int w_key(int row) { return (((row >> 3) & 3) << 1) | ((row >> 1) & 1); }
 
 // OUT_BF16 = false: fp32 partial sums to out[(kz*rows_pad + m)*N + n] for every row of the tile.
-// OUT_BF16 = true : bf16 result to out[m*N + n] for m < M.
+// OUT_BF16 = true : bf16 result to out[m*N + n] for m < M (requires gridDim.z == 1).
 template <bool OUT_BF16>
-__global__ __launch_bounds__(256) void gemm_rows128_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
-                                                           void* __restrict__ out, int M, int K, int N, int k_per_split,
-                                                           int rows_pad)
+__global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_t* __restrict__ X,
+                                                                   const uint16_t* __restrict__ W,
+                                                                   void* __restrict__ out, int M, int K, int N,
+                                                                   int k_per_split, int rows_pad)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char sA[kQProjRows * kLdsRow];
-    __shared__ __attribute__((aligned(16))) unsigned char sW[kTileN * kLdsRow];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const lds_ptr_t lds_base = (lds_ptr_t)smem;
+    const uint32_t lds_addr0 = (uint32_t)(uintptr_t)lds_base;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int n = lane & 15, g = lane >> 4;
-    const int n0 = blockIdx.x * kTileN;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int mp = wave & 3;                  // rows 32*mp .. 32*mp+31 of the 128-row tile
+    const int kh = wave >> 2;                 // takes the k steps of every stage with (step & 1) == kh
+    const int n = lane & 15;
+    const int g = lane >> 4;
+
+    const int n0 = blockIdx.x * kStripN;
     const int m0 = blockIdx.y * kQProjRows;
     const int kz = blockIdx.z;
     const int k_begin = kz * k_per_split;
-    const int k_end = k_begin + k_per_split;
+    const int k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
+    const int n_stages = (k_end - k_begin + kStageRows - 1) / kStageRows;
 
-    f32x4 acc[2][4];
+    // Direct load of one stage of W: 64 loads of 4 rows; wave w issues loads 8w .. 8w+7.
+    auto issue_stage = [&](int stage, int slot) {
+        const int k0 = k_begin + stage * kStageRows;
+        const int rows_valid = (k_end - k0 < kStageRows) ? k_end - k0 : kStageRows;   // multiple of 32
+        const int p16 = lane & 15;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int first_row = 4 * (8 * wave + i);                  // wave-uniform
+            if (first_row < rows_valid) {
+                const int row = first_row + (lane >> 4);
+                const int c16 = ((((p16 >> 1) ^ w_key(row)) << 1) | (p16 & 1));
+                const unsigned char* src = (const unsigned char*)W + ((size_t)(k0 + row) * N + n0) * 2 + c16 * 16;
+                load_to_lds_16B(src, lds_addr0 + slot * kStageBytes + first_row * kRowBytes);
+            }
+        }
+    };
+
+    // x fragments of this wave's k steps of one stage: lane (row n of a 16-row block, k group g)
+    // holds x[row][k0 + 32*(2j + kh) + 8g .. +7].  Every x element is loaded by exactly one wave.
+    constexpr int kMySteps = kStepsPerStage / 2;
+    bf16x8 xf[2][2][kMySteps];                // [buffer][row block][own k step]
+    int xrow[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+        const int r = m0 + 32 * mp + 16 * mb + n;
+        xrow[mb] = r < M ? r : M - 1;         // rows past M repeat the last one; their results are not stored
+    }
+    auto load_x_stage = [&](int stage, int buf) {
+        const int k0 = k_begin + stage * kStageRows;
+#pragma unroll
+        for (int j = 0; j < kMySteps; ++j) {
+            int k = k0 + 32 * (2 * j + kh) + 8 * g;
+            k = k + 8 <= K ? k : K - 8;       // steps past k_end are never used; keep the address inside x
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+                xf[buf][mb][j] = *(const bf16x8*)(X + (size_t)xrow[mb] * K + k);
+        }
+    };
+
+    f32x4 acc[2][8];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < 8; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = k_begin; k0 < k_end; k0 += kStepK) {
-        __syncthreads();
-        // A tile: 128 rows x 32 k, two 16-byte pieces per thread
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int r = (tid >> 2) + 64 * i;
-            const int c = tid & 3;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (m0 + r < M) v = *(const uint4*)(A + (size_t)(m0 + r) * K + k0 + 8 * c);
-            *(uint4*)(sA + r * kLdsRow + 16 * c) = v;
-        }
-        // W tile: 32 k x 64 n, transposed into [n][k] so that a lane reads 8 consecutive k
-        {
-            const int kk = tid >> 3;
-            const int n8 = (tid & 7) * 8;
-            union { uint4 v; uint16_t h[8]; } w;
-            w.v = *(const uint4*)(W + (size_t)(k0 + kk) * N + n0 + n8);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) *(uint16_t*)(sW + (n8 + e) * kLdsRow + 2 * kk) = w.h[e];
-        }
-        __syncthreads();
-        bf16x8 bfrag[4];
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) bfrag[nb] = *(const bf16x8*)(sW + (16 * nb + n) * kLdsRow + 16 * g);
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            const bf16x8 afrag = *(const bf16x8*)(sA + (32 * wave + 16 * mb + n) * kLdsRow + 16 * g);
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag[nb], acc[mb][nb], 0, 0, 0);
-        }
-    }
+    const int a_lane_off = (8 * g + (n >> 2)) * kRowBytes + ((n & 3) << 3);   // row 8g + i, 8 bytes per lane
+    const int a_key = (g << 1) | ((n >> 3) & 1);                             // w_key of rows 8g + 4t + i: 2g + i/2
 
-    // lane holds C[row 4g+i][col n] of each 16x16 block
+    auto compute_stage = [&](int stage, int slot, int buf) {
+        const int k0 = k_begin + stage * kStageRows;
+        const int steps = ((k_end - k0 < kStageRows) ? k_end - k0 : kStageRows) / 32;
+        const int base = slot * kStageBytes;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+        for (int j = 0; j < kMySteps; ++j) {
+            const int ks = 2 * j + kh;
+            if (ks < steps) {
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+                for (int nb = 0; nb < 8; ++nb) {
+                    union { bf16x8 v; s16x4 h[2]; } wf;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int m = m0 + 32 * wave + 16 * mb + 4 * g + i;
-                const int col = n0 + 16 * nb + n;
-                if (OUT_BF16) {
-                    if (m < M) ((__bf16*)out)[(size_t)m * N + col] = (__bf16)acc[mb][nb][i];
-                } else {
-                    ((float*)out)[((size_t)kz * rows_pad + m) * N + col] = acc[mb][nb][i];
+                    for (int t = 0; t < 2; ++t) {
+                        const int off = base + (32 * ks + 4 * t) * kRowBytes + a_lane_off + ((nb ^ a_key) << 5);
+                        wf.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, xf[buf][mb][j], acc[mb][nb], 0, 0, 0);
                 }
             }
+        }
+    };
+
+    issue_stage(0, 0);
+    load_x_stage(0, 0);
+    for (int st = 0; st < n_stages; st += 2) {
+        // even stage: slot 0, x buffer 0
+        wait_vmem_all();
+        __syncthreads();
+        if (st + 1 < n_stages) { issue_stage(st + 1, 1); load_x_stage(st + 1, 1); }
+        compute_stage(st, 0, 0);
+        if (st + 1 >= n_stages) break;
+        // odd stage: slot 1, x buffer 1
+        wait_vmem_all();
+        __syncthreads();
+        if (st + 2 < n_stages) { issue_stage(st + 2, 0); load_x_stage(st + 2, 0); }
+        compute_stage(st + 1, 1, 1);
+    }
+
+    // The two waves that share 32 rows (kh = 0, 1) hold sums over disjoint k steps: exchange halves
+    // through LDS (the stage buffers are dead, no direct load is in flight); kh 0 finishes column
+    // blocks 0..3, kh 1 blocks 4..7.  Fixed order (own + other with kh 0's share first) keeps the
+    // result reproducible.
+    __syncthreads();
+    {
+        const int mine = (mp * 2 + kh) * 8;           // 8 slots of 1 KB: [row block][4 column blocks]
+        const int theirs = (mp * 2 + (kh ^ 1)) * 8;
+        const int send = kh == 0 ? 4 : 0;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const f32x4 v = kh == 0 ? acc[mb][4 + j] : acc[mb][j];
+                *LDS_AT(f32x4, lds_base, (mine + mb * 4 + j) * 1024 + lane * 16) = v;
+            }
+        (void)send;
+        __syncthreads();
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const int m = m0 + 32 * mp + 16 * mb + n;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const f32x4 other = *LDS_AT(f32x4, lds_base, (theirs + mb * 4 + j) * 1024 + lane * 16);
+                const f32x4 own = kh == 0 ? acc[mb][j] : acc[mb][4 + j];
+                const f32x4 r = kh == 0 ? own + other : other + own;     // always (kh 0 part) + (kh 1 part)
+                const int col = n0 + 16 * (4 * kh + j) + 4 * g;
+                if (OUT_BF16) {
+                    if (m < M) {
+                        union { __bf16 h[4]; uint2 u; } o;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o.h[i] = (__bf16)r[i];
+                        *(uint2*)((__bf16*)out + (size_t)m * N + col) = o.u;
+                    }
+                } else {
+                    *(f32x4*)((float*)out + ((size_t)kz * rows_pad + m) * N + col) = r;
+                }
+            }
+        }
+    }
 }
 
-// One workgroup per row of x: c = sum of the split-K partials, c_hat = c / sqrt(mean(c^2) + eps) * gain.
+// One workgroup per row of x: c = sum of the split-K partials (in split order),
+// c_hat = c / sqrt(mean(c^2) + eps) * gain.  A thread owns float4 pieces of the row; the partials
+// of a piece are loaded eight splits at a time so that the loads are in flight together.
 __global__ __launch_bounds__(256) void rmsnorm_reduce_kernel(const float* __restrict__ ws_c, const float* __restrict__ gain,
                                                              __bf16* __restrict__ chat, int r, int split_k, int rows_pad,
                                                              float eps)
 {
     __shared__ float red[4];
+    extern __shared__ float crow[];           // r floats: the reduced row, kept between the two passes
     const int m = blockIdx.x;
     const int tid = threadIdx.x;
+    const size_t split_stride = (size_t)rows_pad * r;
     float ss = 0.f;
-    for (int j = tid; j < r; j += 256) {
-        float c = 0.f;
-        for (int z = 0; z < split_k; ++z) c += ws_c[((size_t)z * rows_pad + m) * r + j];
-        ss += c * c;
+    for (int j = 4 * tid; j < r; j += 1024) {
+        const float* p = ws_c + (size_t)m * r + j;
+        f32x4 c = {0.f, 0.f, 0.f, 0.f};
+        for (int z0 = 0; z0 < split_k; z0 += 8) {
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int z = z0 + u < split_k ? z0 + u : split_k - 1;
+                v[u] = *(const f32x4*)(p + (size_t)z * split_stride);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (z0 + u < split_k) c += v[u];
+        }
+        *(f32x4*)(crow + j) = c;
+        ss += c[0] * c[0] + c[1] * c[1] + c[2] * c[2] + c[3] * c[3];
     }
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
     const float total = red[0] + red[1] + red[2] + red[3];
     const float inv = 1.0f / sqrtf(total / (float)r + eps);
-    for (int j = tid; j < r; j += 256) {
-        float c = 0.f;
-        for (int z = 0; z < split_k; ++z) c += ws_c[((size_t)z * rows_pad + m) * r + j];
-        const float gj = gain ? gain[j] : 1.0f;
-        chat[(size_t)m * r + j] = (__bf16)(c * inv * gj);
+    for (int j = 4 * tid; j < r; j += 1024) {
+        const f32x4 c = *(const f32x4*)(crow + j);
+        union { __bf16 h[4]; uint2 u; } o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o.h[i] = (__bf16)(c[i] * inv * (gain ? gain[j + i] : 1.0f));
+        *(uint2*)(chat + (size_t)m * r + j) = o.u;
     }
 }
 
 }  // namespace
 
-int32_t qproj_split_k(int32_t d_model)
+QProjPlan plan_qproj(int32_t d_model, int32_t q_rank)
 {
-    for (int32_t s = 8; s > 1; --s)
-        if (d_model % (kStepK * s) == 0) return s;
-    return 1;
+    const int32_t strips = q_rank / kStripN;
+    int32_t want = 256 / (strips > 0 ? strips : 1);
+    if (want < 1) want = 1;
+    if (want > 16) want = 16;
+    const int32_t ksteps = d_model / 32;
+    const int32_t per = (ksteps + want - 1) / want;
+    QProjPlan p;
+    p.k_per_split = per * 32;
+    p.split_k = (ksteps + per - 1) / per;
+    return p;
+}
+
+hipError_t prepare_query_proj_kernels()
+{
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_stream_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void*)gemm_stream_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
 }
 
 hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream)
 {
     const int m_blocks = (a.B + kQProjRows - 1) / kQProjRows;
     const int rows_pad = m_blocks * kQProjRows;
-    hipLaunchKernelGGL(gemm_rows128_kernel<false>, dim3(a.q_rank / kTileN, m_blocks, a.split_k), dim3(256), 0, stream,
-                       (const uint16_t*)a.x, (const uint16_t*)a.w_qa, (void*)a.ws_c, a.B, a.d_model, a.q_rank,
-                       a.d_model / a.split_k, rows_pad);
+    hipLaunchKernelGGL(gemm_stream_kernel<false>, dim3(a.q_rank / kStripN, m_blocks, a.split_k), dim3(kGemmThreads),
+                       kGemmLdsBytes, stream, (const uint16_t*)a.x, (const uint16_t*)a.w_qa, (void*)a.ws_c, a.B,
+                       a.d_model, a.q_rank, a.k_per_split, rows_pad);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(rmsnorm_reduce_kernel, dim3(a.B), dim3(256), 0, stream, (const float*)a.ws_c, a.gain,
-                       (__bf16*)a.ws_chat, a.q_rank, a.split_k, rows_pad, a.eps);
+    hipLaunchKernelGGL(rmsnorm_reduce_kernel, dim3(a.B), dim3(256), a.q_rank * sizeof(float), stream,
+                       (const float*)a.ws_c, a.gain, (__bf16*)a.ws_chat, a.q_rank, a.split_k, rows_pad, a.eps);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_rows128_kernel<true>, dim3(a.n_out / kTileN, m_blocks, 1), dim3(256), 0, stream,
-                       (const uint16_t*)a.ws_chat, (const uint16_t*)a.w_qb, a.q_out, a.B, a.q_rank, a.n_out, a.q_rank,
-                       rows_pad);
+    hipLaunchKernelGGL(gemm_stream_kernel<true>, dim3(a.n_out / kStripN, m_blocks, 1), dim3(kGemmThreads),
+                       kGemmLdsBytes, stream, (const uint16_t*)a.ws_chat, (const uint16_t*)a.w_qb, a.q_out, a.B,
+                       a.q_rank, a.n_out, a.q_rank, rows_pad);
     return hipGetLastError();
 }
 
