@@ -61,7 +61,7 @@ struct QProjArgs {
     const void* w_qb;     // bf16 [q_rank,n_out]
     void* q_out;          // bf16 [B,n_out]
     float* ws_c;          // fp32 [split_k][B_pad][q_rank] partial sums of the first product
-    void* ws_chat;        // bf16 [B_pad][q_rank]
+    void* ws_chat;        // bf16, k-step-major: element (m, k) at ((k/32)*B_pad + m)*32 + k%32
     int32_t B, d_model, q_rank, n_out;
     int32_t split_k;
     int32_t k_per_split;  // multiple of 32

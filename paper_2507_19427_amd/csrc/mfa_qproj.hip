@@ -34,7 +34,10 @@ __device__ __forceinline__ int w_key(int row) { return (((row >> 3) & 3) << 1) |
 
 // OUT_BF16 = false: fp32 partial sums to out[(kz*rows_pad + m)*N + n] for every row of the tile.
 // OUT_BF16 = true : bf16 result to out[m*N + n] for m < M (requires gridDim.z == 1).
-template <bool OUT_BF16>
+// X_TILED = false: x is row-major [M, K].
+// X_TILED = true : x is stored k-step-major, element (m, k) at ((k/32)*rows_pad + m)*32 + k%32, so
+//                  that the 16 rows x 64 B a wave loads per k step are contiguous.
+template <bool OUT_BF16, bool X_TILED>
 __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_t* __restrict__ X,
                                                                    const uint16_t* __restrict__ W,
                                                                    void* __restrict__ out, int M, int K, int N,
@@ -92,8 +95,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
             int k = k0 + 32 * (2 * j + kh) + 8 * g;
             k = k + 8 <= K ? k : K - 8;       // steps past k_end are never used; keep the address inside x
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-                xf[buf][mb][j] = *(const bf16x8*)(X + (size_t)xrow[mb] * K + k);
+            for (int mb = 0; mb < 2; ++mb) {
+                const size_t idx = X_TILED ? ((size_t)(k >> 5) * rows_pad + xrow[mb]) * 32 + (k & 31)
+                                           : (size_t)xrow[mb] * K + k;
+                xf[buf][mb][j] = *(const bf16x8*)(X + idx);
+            }
         }
     };
 
@@ -106,27 +112,30 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
     const int a_lane_off = (8 * g + (n >> 2)) * kRowBytes + ((n & 3) << 3);   // row 8g + i, 8 bytes per lane
     const int a_key = (g << 1) | ((n >> 3) & 1);                             // w_key of rows 8g + 4t + i: 2g + i/2
 
+    auto compute_step = [&](int base, int ks, const bf16x8& x0, const bf16x8& x1) {
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+            union { bf16x8 v; s16x4 h[2]; } wf;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int off = base + (32 * ks + 4 * t) * kRowBytes + a_lane_off + ((nb ^ a_key) << 5);
+                wf.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
+            }
+            acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, x0, acc[0][nb], 0, 0, 0);
+            acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, x1, acc[1][nb], 0, 0, 0);
+        }
+    };
     auto compute_stage = [&](int stage, int slot, int buf) {
         const int k0 = k_begin + stage * kStageRows;
         const int steps = ((k_end - k0 < kStageRows) ? k_end - k0 : kStageRows) / 32;
         const int base = slot * kStageBytes;
+        if (steps == kStepsPerStage) {                 // full stage: straight-line code the scheduler can interleave
 #pragma unroll
-        for (int j = 0; j < kMySteps; ++j) {
-            const int ks = 2 * j + kh;
-            if (ks < steps) {
+            for (int j = 0; j < kMySteps; ++j) compute_step(base, 2 * j + kh, xf[buf][0][j], xf[buf][1][j]);
+        } else {
 #pragma unroll
-                for (int nb = 0; nb < 8; ++nb) {
-                    union { bf16x8 v; s16x4 h[2]; } wf;
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const int off = base + (32 * ks + 4 * t) * kRowBytes + a_lane_off + ((nb ^ a_key) << 5);
-                        wf.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
-                    }
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, xf[buf][mb][j], acc[mb][nb], 0, 0, 0);
-                }
-            }
+            for (int j = 0; j < kMySteps; ++j)
+                if (2 * j + kh < steps) compute_step(base, 2 * j + kh, xf[buf][0][j], xf[buf][1][j]);
         }
     };
 
@@ -228,7 +237,7 @@ __global__ __launch_bounds__(256) void rmsnorm_reduce_kernel(const float* __rest
         union { __bf16 h[4]; uint2 u; } o;
 #pragma unroll
         for (int i = 0; i < 4; ++i) o.h[i] = (__bf16)(c[i] * inv * (gain ? gain[j + i] : 1.0f));
-        *(uint2*)(chat + (size_t)m * r + j) = o.u;
+        *(uint2*)(chat + ((size_t)(j >> 5) * rows_pad + m) * 32 + (j & 31)) = o.u;   // k-step-major for the second product
     }
 }
 
@@ -250,16 +259,16 @@ QProjPlan plan_qproj(int32_t d_model, int32_t q_rank)
 
 hipError_t prepare_query_proj_kernels()
 {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_stream_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_stream_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void*)gemm_stream_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    return hipFuncSetAttribute((const void*)gemm_stream_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
 }
 
 hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream)
 {
     const int m_blocks = (a.B + kQProjRows - 1) / kQProjRows;
     const int rows_pad = m_blocks * kQProjRows;
-    hipLaunchKernelGGL(gemm_stream_kernel<false>, dim3(a.q_rank / kStripN, m_blocks, a.split_k), dim3(kGemmThreads),
+    hipLaunchKernelGGL((gemm_stream_kernel<false, false>), dim3(a.q_rank / kStripN, m_blocks, a.split_k), dim3(kGemmThreads),
                        kGemmLdsBytes, stream, (const uint16_t*)a.x, (const uint16_t*)a.w_qa, (void*)a.ws_c, a.B,
                        a.d_model, a.q_rank, a.k_per_split, rows_pad);
     hipError_t e = hipGetLastError();
@@ -268,7 +277,7 @@ hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream)
                        (const float*)a.ws_c, a.gain, (__bf16*)a.ws_chat, a.q_rank, a.split_k, rows_pad, a.eps);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_stream_kernel<true>, dim3(a.n_out / kStripN, m_blocks, 1), dim3(kGemmThreads),
+    hipLaunchKernelGGL((gemm_stream_kernel<true, true>), dim3(a.n_out / kStripN, m_blocks, 1), dim3(kGemmThreads),
                        kGemmLdsBytes, stream, (const uint16_t*)a.ws_chat, (const uint16_t*)a.w_qb, a.q_out, a.B,
                        a.q_rank, a.n_out, a.q_rank, rows_pad);
     return hipGetLastError();
