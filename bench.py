@@ -94,6 +94,20 @@ def main():
     ev_mean = sum(ev_ms) / K
     ev_median = ev_ms[K // 2]
 
+    # Reference: a do-nothing kernel that only reads the same K and V buffers (plain 16-byte loads), timed
+    # the same way.  It bounds what any kernel streaming these bytes can reach on this device.
+    n_ref = min(K, 50)
+    for i in range(3):
+        mfa.mfa_debug_stream_read(ctx, k_sets[i % n_sets], v_sets[i % n_sets])
+    torch.cuda.synchronize()
+    for i in range(n_ref):
+        mfa.mfa_debug_set_kernel_events(ctx, starts[i], stops[i])
+        mfa.mfa_debug_stream_read(ctx, k_sets[i % n_sets], v_sets[i % n_sets])
+    torch.cuda.synchronize()
+    mfa.mfa_debug_set_kernel_events(ctx, None, None)
+    ref_ms = sum(s.elapsed_time(e) for s, e in zip(starts[:n_ref], stops[:n_ref])) / n_ref
+    ref_gbs = T * KV_BYTES_PER_TOKEN / (ref_ms * 1e-3) / 1e9
+
     value = T / (ms_per_step * 1e-3)
     algo_bytes = T * KV_BYTES_PER_TOKEN + B * (Q_BYTES_PER_SEQ + OUT_BYTES_PER_SEQ)
     achieved = algo_bytes / (ev_mean * 1e-3) / 1e9
@@ -125,6 +139,9 @@ def main():
             "event_ms_mean": ev_mean,
             "event_ms_median": ev_median,
             "event_ms_min": ev_ms[0],
+            "plain_read_of_same_kv": {"GBps": ref_gbs, "ms": ref_ms, "frac_of_peak": ref_gbs / HBM_PEAK_GBS,
+                                      "note": "do-nothing kernel reading the same K,V buffers once; "
+                                              "attention kernel / this = %.3f" % (achieved / ref_gbs)},
         },
     }
 

@@ -180,6 +180,16 @@ MFA_API mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_
  */
 MFA_API mfa_status mfa_debug_set_kernel_events(mfa_ctx* ctx, void* ev_before, void* ev_after);
 
+/*
+ * Measurement aid, not part of the serving path: one kernel that reads `bytes_each`
+ * bytes from each of the two device buffers with plain 16-byte loads and computes
+ * nothing, i.e. the time any kernel needs just to stream that many bytes from HBM
+ * on this device.  bytes_each must be a positive multiple of 16 MiB.  Honours the
+ * events set with mfa_debug_set_kernel_events.
+ */
+MFA_API mfa_status mfa_debug_stream_read(mfa_ctx* ctx, const void* a, const void* b, size_t bytes_each,
+                                         void* hip_stream);
+
 /* Number of context splits the next mfa_decode_attn* call with these host
  * arguments would use (each split's partial result is merged by the library).
  * Pure host function; 0 on invalid arguments. */

@@ -25,7 +25,7 @@ MFA_KV_FP8_E4M3 = 1
 EXPORTS = [
     "mfa_decode_workspace_bytes", "mfa_decode_init", "mfa_decode_destroy", "mfa_status_string",
     "mfa_query_proj", "mfa_decode_attn", "mfa_decode_attn_paged", "mfa_debug_gather_paged",
-    "mfa_decode_num_splits", "mfa_debug_set_kernel_events",
+    "mfa_decode_num_splits", "mfa_debug_set_kernel_events", "mfa_debug_stream_read",
 ]
 
 
@@ -92,6 +92,8 @@ def lib():
     L.mfa_debug_gather_paged.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, i64, vp]
     L.mfa_debug_set_kernel_events.restype = ctypes.c_int
     L.mfa_debug_set_kernel_events.argtypes = [vp, vp, vp]
+    L.mfa_debug_stream_read.restype = ctypes.c_int
+    L.mfa_debug_stream_read.argtypes = [vp, vp, vp, sz, vp]
     L.mfa_decode_num_splits.restype = i32
     L.mfa_decode_num_splits.argtypes = [vp, i32, i32]
     _lib = L
@@ -271,6 +273,14 @@ def mfa_debug_set_kernel_events(ctx: MfaContext, ev_before=None, ev_after=None):
     hb = None if ev_before is None else ctypes.c_void_p(ev_before.cuda_event)
     ha = None if ev_after is None else ctypes.c_void_p(ev_after.cuda_event)
     _check(lib().mfa_debug_set_kernel_events(ctx.handle, hb, ha), "mfa_debug_set_kernel_events")
+
+
+def mfa_debug_stream_read(ctx: MfaContext, a, b):
+    """Read the two equally sized device tensors once with a do-nothing kernel (bandwidth ceiling probe)."""
+    nbytes = a.numel() * a.element_size()
+    if b.numel() * b.element_size() != nbytes:
+        raise ValueError("buffers must have equal size")
+    _check(lib().mfa_debug_stream_read(ctx.handle, _ptr(a), _ptr(b), nbytes, _stream()), "mfa_debug_stream_read")
 
 
 class PreparedDecodeAttn:

@@ -197,6 +197,17 @@ mfa_status mfa_debug_set_kernel_events(mfa_ctx* ctx, void* ev_before, void* ev_a
     return MFA_OK;
 }
 
+mfa_status mfa_debug_stream_read(mfa_ctx* ctx, const void* a, const void* b, size_t bytes_each, void* hip_stream)
+{
+    if (!ctx || !a || !b || !aligned16(a) || !aligned16(b)) return MFA_ERR_INVALID_ARG;
+    if (bytes_each == 0 || bytes_each % ((size_t)2048 * 8192) != 0) return MFA_ERR_INVALID_ARG;
+    if (!on_device(ctx)) return MFA_ERR_INVALID_ARG;
+    // the first bytes of the partial-result area serve as the (practically never written) sink
+    const hipError_t e = launch_stream_read(a, b, bytes_each, ctx->ws_acc, static_cast<hipStream_t>(hip_stream),
+                                            ctx->ev_before, ctx->ev_after);
+    return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
 int32_t mfa_decode_num_splits(const mfa_ctx* ctx, int32_t B, int32_t max_seq_len_hint)
 {
     if (!ctx || B < 1 || B > ctx->cfg.max_batch || max_seq_len_hint < 1 || max_seq_len_hint > ctx->cfg.max_seq_len)

@@ -35,14 +35,18 @@ constexpr int kStageBytes = 33792;
 constexpr int kFp8StageBase = kSlotBytes;             // staging ring sits after the bf16 tile image
 constexpr int kFp8LdsBytes = kSlotBytes + 2 * kStageBytes;   // 133120
 
+// Page id of the tile that starts at token tile_t0 (paged cache only).  Looked up one tile ahead
+// of its use so that the table read is never on the critical path of issuing a tile's loads.
 template <bool PAGED>
-__device__ __forceinline__ int64_t tile_row0(const AttnArgs& a, int b, int tile_t0)
+__device__ __forceinline__ int lookup_page(const AttnArgs& a, int b, int tile_t0)
 {
-    if (PAGED) {
-        const int page = a.block_table[(size_t)b * a.max_blocks_per_seq + tile_t0 / kPage];
-        return (int64_t)page * kPage;
-    }
-    return (int64_t)b * a.seq_stride_tokens + tile_t0;
+    return PAGED ? a.block_table[(size_t)b * a.max_blocks_per_seq + tile_t0 / kPage] : 0;
+}
+
+template <bool PAGED>
+__device__ __forceinline__ int64_t tile_row0(const AttnArgs& a, int b, int tile_t0, int page)
+{
+    return PAGED ? (int64_t)page * kPage : (int64_t)b * a.seq_stride_tokens + tile_t0;
 }
 
 template <bool PAGED>
@@ -69,9 +73,9 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     // Wave w brings rows [8w, 8w+8) of the tile's K and V: all in unit w/4.  Rows at or past t1
     // re-read the last valid token, so nothing outside the sequence is touched and every LDS row
     // holds finite data (the weights of those rows are masked to zero).
-    auto issue_tile = [&](int tile, int slot) {
+    auto issue_tile = [&](int tile, int slot, int page) {
         const int tile_t0 = r.t0 + tile * kTile;
-        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0);
+        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, page);
         const int p16 = lane & 31;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -94,12 +98,16 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     WaveState st;
     init_state(st);
 
-    issue_tile(0, 0);
+    issue_tile(0, 0, lookup_page<PAGED>(a, r.b, r.t0));
+    int page_next = r.n_tiles > 1 ? lookup_page<PAGED>(a, r.b, r.t0 + kTile) : 0;
     for (int it = 0; it < r.n_tiles; ++it) {
         const int slot = it & 1;
         wait_vmem_all();
         __syncthreads();
-        if (it + 1 < r.n_tiles) issue_tile(it + 1, slot ^ 1);
+        if (it + 1 < r.n_tiles) {
+            issue_tile(it + 1, slot ^ 1, page_next);
+            if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
+        }
         process_unit<false>(st, qf, lds_base, slot * kSlotBytes + grp * kUnitBytes,
                             r.t0 + it * kTile + grp * kUnitTokens, r.t1, a.scale_log2e, n, g, 0, 0);
     }
@@ -129,9 +137,9 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
 
     // Wave w brings rows [8w, 8w+8) of the tile's K and V codes (256 B per row, 4 rows per load);
     // waves 0 and 1 also bring the 64 key and value scales.
-    auto issue_tile = [&](int tile, int slot) {
+    auto issue_tile = [&](int tile, int slot, int page) {
         const int tile_t0 = r.t0 + tile * kTile;
-        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0);
+        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, page);
         const uint32_t stage = lds_addr0 + kFp8StageBase + slot * kStageBytes;
         const int last = r.t1 - 1 - tile_t0;                          // last valid row of this tile (>= 0)
 #pragma unroll
@@ -187,12 +195,16 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
     WaveState st;
     init_state(st);
 
-    issue_tile(0, 0);
+    issue_tile(0, 0, lookup_page<PAGED>(a, r.b, r.t0));
+    int page_next = r.n_tiles > 1 ? lookup_page<PAGED>(a, r.b, r.t0 + kTile) : 0;
     for (int it = 0; it < r.n_tiles; ++it) {
         const int slot = it & 1;
         wait_vmem_all();
         __syncthreads();          // staged tile `it` landed; everyone is done with the bf16 image of tile it-1
-        if (it + 1 < r.n_tiles) issue_tile(it + 1, slot ^ 1);
+        if (it + 1 < r.n_tiles) {
+            issue_tile(it + 1, slot ^ 1, page_next);
+            if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
+        }
         convert_tile(slot);
         __syncthreads();
         const int stage = kFp8StageBase + slot * kStageBytes;
@@ -277,6 +289,34 @@ __global__ __launch_bounds__(256) void gather_paged_kernel(const uint32_t* pool,
     const uint32_t* src = pool + (size_t)page * kPage * row_words;
     uint32_t* d = dst + ((size_t)b * dst_seq_stride_tokens + tok0) * row_words;
     for (int i = threadIdx.x; i < n_tok * row_words; i += 256) d[i] = src[i];
+}
+
+// Measurement aid: read two buffers once with plain 16-byte loads and do nothing else.  What
+// this reaches is the practical ceiling for any kernel that must stream the same bytes.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
+                                                          size_t n16_per_block, uint32_t* sink)
+{
+    const uint4* pa = a + (size_t)blockIdx.x * n16_per_block;
+    const uint4* pb = b + (size_t)blockIdx.x * n16_per_block;
+    uint32_t acc = 0;
+    for (size_t i = threadIdx.x; i < n16_per_block; i += 512) {
+        const uint4 x0 = pa[i], x1 = pa[i + 256], y0 = pb[i], y1 = pb[i + 256];
+        acc ^= x0.x ^ x0.y ^ x0.z ^ x0.w ^ x1.x ^ x1.y ^ x1.z ^ x1.w ^ y0.x ^ y0.y ^ y0.z ^ y0.w ^ y1.x ^ y1.y ^ y1.z ^ y1.w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;     // keeps the loads alive; practically never true
+}
+
+hipError_t launch_stream_read(const void* a, const void* b, size_t bytes_each, void* sink, hipStream_t stream,
+                              hipEvent_t ev_before, hipEvent_t ev_after)
+{
+    constexpr unsigned kBlocks = 2048;
+    if (ev_before && ev_after && hipEventRecord(ev_before, stream) != hipSuccess) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(kBlocks), dim3(256), 0, stream, (const uint4*)a, (const uint4*)b,
+                       bytes_each / kBlocks / 16, (uint32_t*)sink);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (ev_before && ev_after && hipEventRecord(ev_after, stream) != hipSuccess) return hipErrorInvalidValue;
+    return hipSuccess;
 }
 
 SplitPlan plan_splits(int32_t B, int32_t max_seq_len_hint, int32_t target_items)

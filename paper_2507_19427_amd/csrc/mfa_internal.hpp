@@ -52,7 +52,10 @@ struct AttnArgs {
 // Launchers (enqueue only; return the launch status).
 hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream,
                               hipEvent_t ev_before, hipEvent_t ev_after);   // events may be NULL
-hipError_t prepare_decode_attn_kernels();   // one-time function attributes (dynamic LDS size)
+hipError_t prepare_decode_attn_kernels();
+// bytes_each must be a multiple of 2048 * 8192; sink is 4 writable bytes
+hipError_t launch_stream_read(const void* a, const void* b, size_t bytes_each, void* sink, hipStream_t stream,
+                              hipEvent_t ev_before, hipEvent_t ev_after);   // one-time function attributes (dynamic LDS size)
 
 struct QProjArgs {
     const void* x;        // bf16 [B,d_model]
