@@ -14,12 +14,14 @@
 // unit images).  The XOR swizzle of the unit image is applied on the global side
 // of the direct load because its LDS side is fixed to base + 16*lane.
 //
-// fp8 cache (OCP e4m3, one fp32 scale per token per tensor): the codes and scales
-// of a tile are brought in the same way into a two-slot staging ring (33 KB per
-// slot); the whole workgroup then converts the codes once to bf16 (exact) into a
-// single bf16 tile image, and the same MFMA path runs on it.  The key scale
+// fp8 cache (OCP e4m3, one fp32 scale per token per tensor): the codes of a tile
+// travel through registers (plain coalesced 16-byte loads, two tiles ahead), the
+// whole workgroup converts them once to bf16 (exact) into one of two bf16 tile
+// images in LDS, and the same MFMA path runs on the image.  The key scale
 // multiplies the score column of its token, the value scale rides on the
 // attention weight of its token.
+#include <type_traits>
+
 #include "mfa_attn_core.hpp"
 
 namespace mfa {
@@ -27,13 +29,9 @@ namespace mfa {
 constexpr int kSlotBytes = 2 * kUnitBytes;            // one 64-token tile: two unit images
 constexpr int kAttnLdsBytes = 2 * kSlotBytes;         // bf16 kernel: 128 KB
 
-constexpr int kStageK = 0;                            // fp8 staging slot: K codes 64x256 B
-constexpr int kStageV = 16384;                        //                   V codes 64x256 B
-constexpr int kStageKScale = 32768;                   //                   64 fp32 key scales
-constexpr int kStageVScale = 33024;                   //                   64 fp32 value scales
-constexpr int kStageBytes = 33792;
-constexpr int kFp8StageBase = kSlotBytes;             // staging ring sits after the bf16 tile image
-constexpr int kFp8LdsBytes = kSlotBytes + 2 * kStageBytes;   // 133120
+// fp8 kernel: two bf16 tile images, then per image 64 key scales and 64 value scales (fp32)
+constexpr int kFp8ScaleBase = 2 * kSlotBytes;
+constexpr int kFp8LdsBytes = 2 * kSlotBytes + 2 * 512;
 
 // Page id of the tile that starts at token tile_t0 (paged cache only).  Looked up one tile ahead
 // of its use so that the table read is never on the critical path of issuing a tile's loads.
@@ -114,12 +112,40 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     finish_item(st, lds_base, a, r.b, item, wq, grp, lane);
 }
 
+// One tile of fp8 codes held in registers on its way from HBM to the bf16 LDS image: the
+// workgroup's 512 threads each own four 16-byte pieces (two of K, two of V) and, for the first
+// 128 threads, one per-token scale.
+struct Fp8TileRegs {
+    u32x4 piece[4];
+    float scale;
+};
+constexpr int kFp8LoadsPerTile = 5;
+
+// The loads of the register pipeline are issued as inline assembly and awaited with an explicit
+// vmcnt that leaves exactly the newer tile's loads in flight; left to the compiler, the wait for the
+// older tile is widened to vmcnt(0) at the loop's control-flow joins, which drains the pipeline every
+// tile.  wait_tile() passes the registers through the waiting statement, so no use of them can be
+// scheduled before it.
+__device__ __forceinline__ void load_regs_16B(u32x4& dst, const void* p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void load_regs_4B(float& dst, const void* p)
+{
+    asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void wait_tile_older_of_two(Fp8TileRegs& t)
+{
+    static_assert(kFp8LoadsPerTile == 5, "the wait below leaves 5 loads in flight");
+    asm volatile("s_waitcnt vmcnt(5)"
+                 : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.piece[2]), "+v"(t.piece[3]), "+v"(t.scale) :: "memory");
+}
+
 template <bool PAGED>
 __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const lds_ptr_t lds_base = (lds_ptr_t)smem;
-    const uint32_t lds_addr0 = (uint32_t)(uintptr_t)lds_base;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -132,85 +158,97 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
     const ItemRange r = item_range(a, item);
     if (r.t0 >= r.t1) { empty_item(a, r); return; }
 
-    bf16x8 qf[8];
-    load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
-
-    // Wave w brings rows [8w, 8w+8) of the tile's K and V codes (256 B per row, 4 rows per load);
-    // waves 0 and 1 also bring the 64 key and value scales.
-    auto issue_tile = [&](int tile, int slot, int page) {
+    // Piece i of this thread: tensor (i >> 1 ? V : K), row (threadIdx.x >> 4) + 32*(i & 1), 16-byte
+    // chunk threadIdx.x & 15, so that consecutive threads read consecutive 16 bytes.  Rows at or
+    // past t1 re-read the last valid token.
+    const int prow = threadIdx.x >> 4;
+    const int pchunk = threadIdx.x & 15;
+    auto load_tile = [&](Fp8TileRegs& t, int tile) {
+        if (tile >= r.n_tiles) tile = r.n_tiles - 1;   // past the end: re-read the last tile (never consumed)
         const int tile_t0 = r.t0 + tile * kTile;
-        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, page);
-        const uint32_t stage = lds_addr0 + kFp8StageBase + slot * kStageBytes;
+        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, lookup_page<PAGED>(a, r.b, tile_t0));
         const int last = r.t1 - 1 - tile_t0;                          // last valid row of this tile (>= 0)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int row = 8 * wave + 4 * j + (lane >> 4);
+        for (int i = 0; i < 4; ++i) {
+            const int row = prow + 32 * (i & 1);
             const int in_tile = row > last ? last : row;
-            const size_t goff = (size_t)(row0 + in_tile) * 256 + (lane & 15) * 16;
-            load_to_lds_16B((const unsigned char*)a.k + goff, stage + kStageK + (8 * wave + 4 * j) * 256);
-            load_to_lds_16B((const unsigned char*)a.v + goff, stage + kStageV + (8 * wave + 4 * j) * 256);
+            const unsigned char* base = (const unsigned char*)((i >> 1) ? a.v : a.k);
+            load_regs_16B(t.piece[i], base + (size_t)(row0 + in_tile) * 256 + pchunk * 16);
         }
-        if (wave < 2) {
-            const int in_tile = lane > last ? last : lane;
-            const float* src = (wave == 0 ? a.k_scale : a.v_scale) + (row0 + in_tile);
-            load_to_lds_4B(src, stage + (wave == 0 ? kStageKScale : kStageVScale));
+        {
+            // every thread loads a scale (threads 128.. repeat those of 0..127) so that the loads of a
+            // tile form one straight-line group: the wait for an older tile can then leave the newer
+            // tile's loads in flight
+            const int tok = threadIdx.x & 63;
+            const int in_tile = tok > last ? last : tok;
+            load_regs_4B(t.scale, ((threadIdx.x & 64) ? a.v_scale : a.k_scale) + (row0 + in_tile));
         }
     };
 
-    // Convert the staged codes of one tile to the swizzled bf16 unit images (exact: every e4m3
-    // value is a bf16 value).  2048 pieces of 16 codes, 4 per thread.
-    auto convert_tile = [&](int slot) {
-        const int stage = kFp8StageBase + slot * kStageBytes;
+    // Convert a tile's codes to bf16 (exact: every e4m3 value is a bf16 value) and write them into
+    // image `slot` in the swizzled unit layout; the scales go beside it.
+    auto store_tile = [&](const Fp8TileRegs& t, int slot) {
+        const int image = slot * kSlotBytes;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int piece = threadIdx.x + kAttnThreads * i;
-            const int is_v = piece >> 10;
-            const int row = (piece >> 4) & 63;
-            const int c = piece & 15;
-            const u32x4 in = *LDS_AT(u32x4, lds_base, stage + is_v * kStageV + row * 256 + c * 16);
             bf16x8 half[2];
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], false);
-                const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], true);
+                const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], false);
+                const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], true);
                 half[w >> 1][4 * (w & 1) + 0] = (__bf16)f01[0];
                 half[w >> 1][4 * (w & 1) + 1] = (__bf16)f01[1];
                 half[w >> 1][4 * (w & 1) + 2] = (__bf16)f23[0];
                 half[w >> 1][4 * (w & 1) + 3] = (__bf16)f23[1];
             }
-            const int rr = row & 31;
-            const int key = rr & 15;
-            const int unit = (row >> 5) * kUnitBytes + rr * 512;
-            if (is_v) {
-                const int off = unit + kUnitVOffset + ((c ^ key) << 5);
+            const int key = prow & 15;                                 // row within its unit = prow (0..31)
+            const int unit = image + (i & 1) * kUnitBytes + prow * 512;
+            if (i >> 1) {
+                const int off = unit + kUnitVOffset + ((pchunk ^ key) << 5);
                 *LDS_AT(bf16x8, lds_base, off) = half[0];
                 *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
             } else {
-                *LDS_AT(bf16x8, lds_base, unit + (((2 * c) ^ key) << 4)) = half[0];
-                *LDS_AT(bf16x8, lds_base, unit + (((2 * c + 1) ^ key) << 4)) = half[1];
+                *LDS_AT(bf16x8, lds_base, unit + (((2 * pchunk) ^ key) << 4)) = half[0];
+                *LDS_AT(bf16x8, lds_base, unit + (((2 * pchunk + 1) ^ key) << 4)) = half[1];
             }
         }
+        if (threadIdx.x < 128) *LDS_AT(float, lds_base, kFp8ScaleBase + slot * 512 + threadIdx.x * 4) = t.scale;
     };
 
     WaveState st;
     init_state(st);
 
-    issue_tile(0, 0, lookup_page<PAGED>(a, r.b, r.t0));
-    int page_next = r.n_tiles > 1 ? lookup_page<PAGED>(a, r.b, r.t0 + kTile) : 0;
-    for (int it = 0; it < r.n_tiles; ++it) {
-        const int slot = it & 1;
-        wait_vmem_all();
-        __syncthreads();          // staged tile `it` landed; everyone is done with the bf16 image of tile it-1
-        if (it + 1 < r.n_tiles) {
-            issue_tile(it + 1, slot ^ 1, page_next);
-            if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
-        }
-        convert_tile(slot);
-        __syncthreads();
-        const int stage = kFp8StageBase + slot * kStageBytes;
-        process_unit<true>(st, qf, lds_base, grp * kUnitBytes, r.t0 + it * kTile + grp * kUnitTokens, r.t1,
-                           a.scale_log2e, n, g, stage + kStageKScale + grp * kUnitTokens * 4,
-                           stage + kStageVScale + grp * kUnitTokens * 4);
+    // Pipeline: tile t+2 (and t+3) travel from HBM to registers while tile t+1 is converted into the
+    // other LDS image and tile t is consumed from its image; one barrier per tile.
+    Fp8TileRegs regs[2];
+    // The loads of every step are issued unconditionally (clamped to the last tile) so that exactly
+    // two tiles' loads are outstanding whenever one is awaited.
+    load_tile(regs[0], 0);
+    load_tile(regs[1], 1);
+    // The query fragments are loaded by ordinary loads and pinned here: the compiler completes them
+    // (and with them the two tiles above) before the loop, instead of waiting for them, and so for
+    // every load in flight, inside it.
+    bf16x8 qf[8];
+    load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
+    asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7]));
+    wait_tile_older_of_two(regs[0]);
+    store_tile(regs[0], 0);
+    load_tile(regs[0], 2);
+
+    auto step = [&](auto parity_c, int t) {
+        constexpr int P = decltype(parity_c)::value;                    // t & 1
+        __syncthreads();              // image P holds tile t; everyone is done with image P^1 (tile t-1)
+        wait_tile_older_of_two(regs[P ^ 1]);
+        store_tile(regs[P ^ 1], P ^ 1);                                 // tile t+1 (a repeat of the last tile at the end)
+        load_tile(regs[P ^ 1], t + 3);
+        const int scales = kFp8ScaleBase + P * 512 + grp * kUnitTokens * 4;
+        process_unit<true>(st, qf, lds_base, P * kSlotBytes + grp * kUnitBytes, r.t0 + t * kTile + grp * kUnitTokens,
+                           r.t1, a.scale_log2e, n, g, scales, scales + 256);
+    };
+    for (int t = 0; t < r.n_tiles; t += 2) {
+        step(std::integral_constant<int, 0>{}, t);
+        if (t + 1 >= r.n_tiles) break;
+        step(std::integral_constant<int, 1>{}, t + 1);
     }
     finish_item(st, lds_base, a, r.b, item, wq, grp, lane);
 }
