@@ -1,14 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the decode-step MFA attention on one MI355X.
 
-Workload (benchmark configs[1]): batch 64, 64 query heads, one shared K/V head, head dim 256,
-every sequence at context 4096, contiguous bf16 cache, synthetic N(0,1) values from a fixed seed.
-A step is one mfa_decode_attn call (stream the cache once, scores, online softmax, weighted sum,
-merge of the context splits).  Inputs are resident in HBM before the timed region; the cache is
-rotated over several distinct buffer sets so that the 256 MB memory-side cache cannot serve it.
+Default workload (the one the metric is quoted on): batch 64, 64 query heads, one shared K/V head,
+head dim 256, every sequence at context 4096, contiguous bf16 cache, synthetic N(0,1) values from a
+fixed seed.  A step is one pass of the hot path over one batch: one mfa_decode_attn call (stream the
+cache once, scores, online softmax, weighted sum, merge of the context splits); for the workload with
+the query path, mfa_query_proj followed by the attention call.  Inputs are resident in HBM before the
+timed region; the cache is rotated over several distinct buffer sets so that the 256 MB memory-side
+cache cannot serve it.
+
+--workload selects one of the other seeded workloads (ragged paged, long context, query path + fp8
+cache); they exist so that kernel profiles of those shapes can be taken with this same program.
 
 Prints ONE JSON line: metric/value = KV tokens per second, plus
-  roofline      HBM roofline of the attention kernel from HIP-event timings taken in the timed region
+  roofline      HBM roofline of the streaming attention kernel from HIP-event timings taken in the timed region
   cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample of the same workload
 """
 import argparse
@@ -21,13 +26,104 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published peak
-# HBM bytes per launch of the streaming kernel on this workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE scaled by what the same counters read for a 256 MiB device copy
+# HBM bytes per launch of the streaming kernel on the default workload, from rocprofv3 --pmc FETCH_SIZE
+# and WRITE_SIZE scaled by what the same counters read for a 256 MiB device copy
 # (profiles/decode_attn_cfg2_b64_ctx4096_hbm_traffic.md): 276.96 MB read + 16.91 MB written.
-MEASURED_TRAFFIC_BYTES = 135236 * 2.000 * 1024 + 16512 * 1.000 * 1024
-KV_BYTES_PER_TOKEN = 1024      # bf16: 256 key + 256 value elements, 2 bytes each
+MEASURED_TRAFFIC_BYTES = {"cfg2": 135236 * 2.000 * 1024 + 16512 * 1.000 * 1024}
 Q_BYTES_PER_SEQ = 64 * 256 * 2
 OUT_BYTES_PER_SEQ = 64 * 256 * 4
+STREAM_READ_GRANULE = 2048 * 8192      # the plain-read probe takes multiples of this many bytes per buffer
+
+
+class Workload:
+    """What one step runs, and the figures the report needs."""
+    def __init__(self):
+        self.key = self.desc = self.metric = self.dtype = self.kernel = None
+        self.steps = []            # one callable per buffer set
+        self.read_pairs = []       # (K buffer, V buffer) per set for the plain-read reference, or empty
+        self.T = 0                 # KV tokens per step
+        self.kv_bytes_per_token = 0
+        self.B = 0
+        self.extra_config = {}
+        self.case = None           # host case for the oracle sample (contiguous bf16 only)
+        self.keep = []
+
+
+def _roll_sets(t, n_sets):
+    import torch
+    if t.element_size() == 1:                         # roll has no 8-bit float kernel: roll the bytes
+        return [t] + [torch.roll(t.view(torch.uint8), shifts=i, dims=0).contiguous().view(t.dtype)
+                      for i in range(1, n_sets)]
+    return [t] + [torch.roll(t, shifts=i, dims=0).contiguous() for i in range(1, n_sets)]
+
+
+def build_workload(key, mfa, W, n_sets):
+    import torch
+    w = Workload()
+    w.key = key
+    if key in ("cfg2", "cfg4"):
+        case = W.config2_step3(poison=False) if key == "cfg2" else W.config4_long(poison=False)
+        B, S = case.B, case.k.shape[1]
+        w.ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=S))
+        q, lens = case.q.cuda(), case.seq_lens.cuda()
+        ks, vs = _roll_sets(case.k.cuda(), n_sets), _roll_sets(case.v.cuda(), n_sets)
+        out = torch.empty(B, 64, 256, dtype=torch.float32, device="cuda")
+        # one prepared call per buffer set: the timed loop only crosses the C boundary
+        w.steps = [mfa.PreparedDecodeAttn(w.ctx, q, ks[j], vs[j], lens, S, out) for j in range(n_sets)]
+        w.read_pairs = list(zip(ks, vs))
+        w.desc = ("configs[%d]: B=%d, 64 q heads, 1 shared K/V head, head_dim 256, ctx %d, contiguous bf16 KV"
+                  % (1 if key == "cfg2" else 3, B, S))
+        w.metric = "KV tokens/s, MFA decode attention, B=%d, ctx %d, bf16, 1 GPU" % (B, S)
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<false>", 1024
+        w.T, w.B, w.case = case.kv_tokens, B, case
+        w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S)}
+    elif key == "cfg3":
+        case = W.config3_ragged_paged(poison=False)
+        B, S = case.B, int(case.seq_lens.max())
+        w.ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=8192))
+        q, lens, table = case.q.cuda(), case.seq_lens.cuda(), case.block_table.cuda()
+        kp, vp = case.k_pool.cuda(), case.v_pool.cuda()
+        ks = [kp] + [kp.clone() for _ in range(1, n_sets)]     # same pages and table, distinct memory
+        vs = [vp] + [vp.clone() for _ in range(1, n_sets)]
+        out = torch.empty(B, 64, 256, dtype=torch.float32, device="cuda")
+        w.steps = [(lambda j=j: mfa.mfa_decode_attn_paged(w.ctx, q, ks[j], vs[j], table, lens, S, out=out))
+                   for j in range(n_sets)]
+        w.desc = ("configs[2]: B=128, ctx uniform in [1024, 8192], 64-token pages behind a permuted block table, "
+                  "bf16 KV")
+        w.metric = "KV tokens/s, MFA decode attention, B=128, ragged paged ctx 1K-8K, bf16, 1 GPU"
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<true>", 1024
+        w.T, w.B = case.kv_tokens, B
+        w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S), "max_ctx": S}
+    elif key == "cfg5":
+        qc = W.config5_query()
+        B = qc.x.shape[0]
+        w.ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=8192))
+        x, w_qa, w_qb = qc.x.cuda(), qc.w_qa.cuda(), qc.w_qb.cuda()
+        q = mfa.mfa_query_proj(w.ctx, x, w_qa, w_qb)
+        case = W.config5_fp8_cache(q.cpu(), poison=False)
+        S = case.k.shape[1]
+        lens = case.seq_lens.cuda()
+        ks, vs = _roll_sets(case.k.cuda(), n_sets), _roll_sets(case.v.cuda(), n_sets)
+        kss, vss = _roll_sets(case.k_scale.cuda(), n_sets), _roll_sets(case.v_scale.cuda(), n_sets)
+        out = torch.empty(B, 64, 256, dtype=torch.float32, device="cuda")
+        attn = [mfa.PreparedDecodeAttn(w.ctx, q, ks[j], vs[j], lens, S, out, k_scale=kss[j], v_scale=vss[j])
+                for j in range(n_sets)]
+
+        def step(j):
+            mfa.mfa_query_proj(w.ctx, x, w_qa, w_qb, q_out=q)
+            attn[j]()
+        w.steps = [(lambda j=j: step(j)) for j in range(n_sets)]
+        w.read_pairs = list(zip(ks, vs))
+        w.desc = ("configs[4]: B=128, query path 7168 -> 2048 -> RMSNorm -> 64x256, then attention over ctx 8192 of "
+                  "fp8 e4m3 KV with per-token fp32 scales")
+        w.metric = "KV tokens/s, MFA query path + decode attention, B=128, ctx 8192, fp8 KV, 1 GPU"
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16 (fp8 e4m3 KV storage)", "mfa::decode_fp8_kernel<false>", 520
+        w.T, w.B = case.kv_tokens, B
+        w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S)}
+        w.keep = [x, w_qa, w_qb]
+    else:
+        raise ValueError(key)
+    return w
 
 
 def main():
@@ -35,9 +131,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--buffer-sets", type=int, default=5, help="distinct KV buffer sets rotated through")
+    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5"), default="cfg2")
+    ap.add_argument("--buffer-sets", type=int, default=None, help="distinct KV buffer sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
+    ap.add_argument("--calibration-copy", type=int, default=0, metavar="N",
+                    help="after the timed steps, run N device-to-device copies of 256 MiB: a kernel of known HBM "
+                         "traffic beside which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's share of the data-parallel decode path; "
@@ -51,27 +151,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    case = W.config2_step3(poison=False)
-    B, S = case.B, case.k.shape[1]
-    T = case.kv_tokens
-    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=S))
-    n_splits = mfa.mfa_decode_num_splits(ctx, B, S)
-
-    q = case.q.cuda()
-    lens = case.seq_lens.cuda()
-    n_sets = max(1, args.buffer_sets)
-    k_sets = [case.k.cuda()]
-    v_sets = [case.v.cuda()]
-    for i in range(1, n_sets):                       # further sets: the same values, rolled along the batch axis
-        k_sets.append(torch.roll(k_sets[0], shifts=i, dims=0).contiguous())
-        v_sets.append(torch.roll(v_sets[0], shifts=i, dims=0).contiguous())
-    out = torch.empty(B, 64, 256, dtype=torch.float32, device="cuda")
-
-    # one prepared call per buffer set: the timed loop only crosses the C boundary
-    calls = [mfa.PreparedDecodeAttn(ctx, q, k_sets[j], v_sets[j], lens, S, out) for j in range(n_sets)]
+    n_sets = max(1, args.buffer_sets if args.buffer_sets is not None else (5 if args.workload == "cfg2" else 3))
+    w = build_workload(args.workload, mfa, W, n_sets)
+    ctx, T = w.ctx, w.T
 
     for i in range(args.warmup):
-        calls[i % n_sets]()
+        w.steps[i % n_sets]()
     torch.cuda.synchronize()
 
     # HIP events recorded by the library right before and after the streaming kernel of each step
@@ -85,7 +170,7 @@ def main():
     t0 = time.perf_counter()
     for i in range(K):
         mfa.mfa_debug_set_kernel_events(ctx, starts[i], stops[i])
-        calls[i % n_sets]()
+        w.steps[i % n_sets]()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     mfa.mfa_debug_set_kernel_events(ctx, None, None)
@@ -94,25 +179,56 @@ def main():
     ev_mean = sum(ev_ms) / K
     ev_median = ev_ms[K // 2]
 
-    # Reference: a do-nothing kernel that only reads the same K and V buffers (plain 16-byte loads), timed
-    # the same way.  It bounds what any kernel streaming these bytes can reach on this device.
-    n_ref = min(K, 50)
-    for i in range(3):
-        mfa.mfa_debug_stream_read(ctx, k_sets[i % n_sets], v_sets[i % n_sets])
-    torch.cuda.synchronize()
-    for i in range(n_ref):
-        mfa.mfa_debug_set_kernel_events(ctx, starts[i], stops[i])
-        mfa.mfa_debug_stream_read(ctx, k_sets[i % n_sets], v_sets[i % n_sets])
-    torch.cuda.synchronize()
-    mfa.mfa_debug_set_kernel_events(ctx, None, None)
-    ref_ms = sum(s.elapsed_time(e) for s, e in zip(starts[:n_ref], stops[:n_ref])) / n_ref
-    ref_gbs = T * KV_BYTES_PER_TOKEN / (ref_ms * 1e-3) / 1e9
+    if args.calibration_copy > 0:
+        src = torch.randint(0, 255, (256 << 20,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.calibration_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     value = T / (ms_per_step * 1e-3)
-    algo_bytes = T * KV_BYTES_PER_TOKEN + B * (Q_BYTES_PER_SEQ + OUT_BYTES_PER_SEQ)
+    algo_bytes = T * w.kv_bytes_per_token + w.B * (Q_BYTES_PER_SEQ + OUT_BYTES_PER_SEQ)
     achieved = algo_bytes / (ev_mean * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm",
+        "kernel": w.kernel + " (HIP events recorded around it inside the attention call)",
+        "achieved": achieved,
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(w.key),
+        "algorithmic_bytes_per_launch": algo_bytes,
+        "event_ms_mean": ev_mean,
+        "event_ms_median": ev_median,
+        "event_ms_min": ev_ms[0],
+    }
+
+    # Reference: a do-nothing kernel that only reads the same K and V buffers (plain 16-byte loads), timed
+    # the same way.  It bounds what any kernel streaming these bytes can reach on this device.
+    if w.read_pairs:
+        nbytes = w.read_pairs[0][0].numel() * w.read_pairs[0][0].element_size()
+        if nbytes % STREAM_READ_GRANULE == 0:
+            n_ref = min(K, 50)
+            for i in range(3):
+                mfa.mfa_debug_stream_read(ctx, *w.read_pairs[i % n_sets])
+            torch.cuda.synchronize()
+            for i in range(n_ref):
+                mfa.mfa_debug_set_kernel_events(ctx, starts[i], stops[i])
+                mfa.mfa_debug_stream_read(ctx, *w.read_pairs[i % n_sets])
+            torch.cuda.synchronize()
+            mfa.mfa_debug_set_kernel_events(ctx, None, None)
+            ref_ms = sum(s.elapsed_time(e) for s, e in zip(starts[:n_ref], stops[:n_ref])) / n_ref
+            ref_gbs = 2 * nbytes / (ref_ms * 1e-3) / 1e9
+            kv_gbs = 2 * nbytes / (ev_mean * 1e-3) / 1e9
+            roofline["plain_read_of_same_kv"] = {
+                "GBps": ref_gbs, "ms": ref_ms, "frac_of_peak": ref_gbs / HBM_PEAK_GBS,
+                "note": "do-nothing kernel reading the same K,V buffers once; attention kernel's rate over those "
+                        "bytes / this = %.3f" % (kv_gbs / ref_gbs)}
+
+    cfg = {"workload": w.desc, "kv_tokens_per_step": T, "kv_buffer_sets": n_sets}
+    cfg.update(w.extra_config)
     result = {
-        "metric": "KV tokens/s, MFA decode attention, B=64, ctx 4096, bf16, 1 GPU",
+        "metric": w.metric,
         "value": value,
         "unit": "KV tokens/s",
         "n_gpus": 1,
@@ -122,38 +238,19 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": "configs[1]: B=64, 64 q heads, 1 shared K/V head, head_dim 256, ctx 4096, "
-                               "contiguous bf16 KV", "kv_tokens_per_step": T, "n_splits": n_splits,
-                   "kv_buffer_sets": n_sets},
-        "roofline": {
-            "bound": "hbm",
-            "kernel": "mfa::decode_bf16_kernel<false> (HIP events recorded around it inside mfa_decode_attn)",
-            "achieved": achieved,
-            "peak": HBM_PEAK_GBS,
-            "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES,
-            "algorithmic_bytes_per_launch": algo_bytes,
-            "event_ms_mean": ev_mean,
-            "event_ms_median": ev_median,
-            "event_ms_min": ev_ms[0],
-            "plain_read_of_same_kv": {"GBps": ref_gbs, "ms": ref_ms, "frac_of_peak": ref_gbs / HBM_PEAK_GBS,
-                                      "note": "do-nothing kernel reading the same K,V buffers once; "
-                                              "attention kernel / this = %.3f" % (achieved / ref_gbs)},
-        },
+        "config": cfg,
+        "roofline": roofline,
     }
-
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(case, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(w.case, args.cpu_seconds) if w.case is not None else None
     print(json.dumps(result), flush=True)
     ctx.close()
 
 
 def cpu_baseline(case, target_seconds):
     """Time the CPU oracle, as it stands, on the first sequences of the same workload."""
-    import numpy as np
     from oracle import mfa_oracle as O
     b = O.bits_of
     threads = O.get_threads()

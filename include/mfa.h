@@ -173,10 +173,11 @@ MFA_API mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_
 /*
  * Measurement aid, not part of the serving path: while both handles are non-NULL
  * (hipEvent_t passed as void*, created by the caller with timing enabled), every
- * mfa_decode_attn / mfa_decode_attn_paged call on this context records
- * `ev_before` on the call's stream immediately before its streaming kernel (the
- * one that reads the cache) and `ev_after` immediately after it, so the caller
- * can time that kernel alone with hipEventElapsedTime.  Pass NULLs to stop.
+ * mfa_decode_attn / mfa_decode_attn_paged call on this context attaches the two
+ * events to the dispatch of its streaming kernel (the one that reads the cache)
+ * on the call's stream: `ev_before` takes the time that kernel starts on the
+ * device and `ev_after` the time it ends, so hipEventElapsedTime(ev_before,
+ * ev_after) is the duration of that kernel alone.  Pass NULLs to stop.
  */
 MFA_API mfa_status mfa_debug_set_kernel_events(mfa_ctx* ctx, void* ev_before, void* ev_after);
 

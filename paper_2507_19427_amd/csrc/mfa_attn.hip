@@ -20,6 +20,7 @@
 // images in LDS, and the same MFMA path runs on the image.  The key scale
 // multiplies the score column of its token, the value scale rides on the
 // attention weight of its token.
+#include <hip/hip_ext.h>
 #include <type_traits>
 
 #include "mfa_attn_core.hpp"
@@ -348,13 +349,10 @@ hipError_t launch_stream_read(const void* a, const void* b, size_t bytes_each, v
                               hipEvent_t ev_before, hipEvent_t ev_after)
 {
     constexpr unsigned kBlocks = 2048;
-    if (ev_before && ev_after && hipEventRecord(ev_before, stream) != hipSuccess) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(stream_read_kernel, dim3(kBlocks), dim3(256), 0, stream, (const uint4*)a, (const uint4*)b,
-                       bytes_each / kBlocks / 16, (uint32_t*)sink);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (ev_before && ev_after && hipEventRecord(ev_after, stream) != hipSuccess) return hipErrorInvalidValue;
-    return hipSuccess;
+    if (!(ev_before && ev_after)) ev_before = ev_after = nullptr;
+    hipExtLaunchKernelGGL(stream_read_kernel, dim3(kBlocks), dim3(256), 0, stream, ev_before, ev_after, 0,
+                          (const uint4*)a, (const uint4*)b, bytes_each / kBlocks / 16, (uint32_t*)sink);
+    return hipGetLastError();
 }
 
 SplitPlan plan_splits(int32_t B, int32_t max_seq_len_hint, int32_t target_items)
@@ -389,17 +387,18 @@ hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStrea
     const dim3 grid((unsigned)(a.B * a.n_splits));
     const dim3 block(kAttnThreads);
     if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return hipErrorNotSupported;
-    if (ev_before && ev_after && hipEventRecord(ev_before, stream) != hipSuccess) return hipErrorInvalidValue;
+    // The two events, when given, are attached to the streaming kernel's own dispatch: they take the
+    // times at which that kernel starts and ends on the device, with no launch gap inside the interval.
+    if (!(ev_before && ev_after)) ev_before = ev_after = nullptr;
     if (kv_dtype == MFA_KV_BF16) {
-        if (a.block_table) hipLaunchKernelGGL(decode_bf16_kernel<true>, grid, block, kAttnLdsBytes, stream, a);
-        else               hipLaunchKernelGGL(decode_bf16_kernel<false>, grid, block, kAttnLdsBytes, stream, a);
+        if (a.block_table) hipExtLaunchKernelGGL(decode_bf16_kernel<true>, grid, block, kAttnLdsBytes, stream, ev_before, ev_after, 0, a);
+        else               hipExtLaunchKernelGGL(decode_bf16_kernel<false>, grid, block, kAttnLdsBytes, stream, ev_before, ev_after, 0, a);
     } else {
-        if (a.block_table) hipLaunchKernelGGL(decode_fp8_kernel<true>, grid, block, kFp8LdsBytes, stream, a);
-        else               hipLaunchKernelGGL(decode_fp8_kernel<false>, grid, block, kFp8LdsBytes, stream, a);
+        if (a.block_table) hipExtLaunchKernelGGL(decode_fp8_kernel<true>, grid, block, kFp8LdsBytes, stream, ev_before, ev_after, 0, a);
+        else               hipExtLaunchKernelGGL(decode_fp8_kernel<false>, grid, block, kFp8LdsBytes, stream, ev_before, ev_after, 0, a);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (ev_before && ev_after && hipEventRecord(ev_after, stream) != hipSuccess) return hipErrorInvalidValue;
     if (a.n_splits > 1) {
         const unsigned blocks = (unsigned)(((size_t)a.B * kHeads * (kHeadDim / 4) + 255) / 256);
         hipLaunchKernelGGL(merge_splits_kernel, dim3(blocks), dim3(256), 0, stream, a);
