@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <new>
+#include <string>
 
 #include "mfa_internal.hpp"
 
@@ -10,10 +11,12 @@ using namespace mfa;
 
 struct mfa_ctx {
     mfa_config cfg;
-    int32_t target_items;      // work items the split planner aims for (one per compute unit by default)
+    int32_t target_items;      // workgroups the planner aims for (one per compute unit by default)
+    bool fixed_splits;         // MFA_SCHEDULE=fixed: every sequence cut into the same number of equal chunks
     size_t max_items;          // bound on B * n_splits over all admissible calls
     float* ws_acc;
     float* ws_ml;
+    int32_t* ws_seg;
     float* ws_c;
     void* ws_chat;
     QProjPlan qproj;
@@ -62,13 +65,15 @@ size_t max_items_for(const mfa_config* c, int32_t target)
         const size_t items = (size_t)B * p.n_splits;
         if (items > best) best = items;
     }
-    return best;
+    const int32_t Bb = c->max_batch < kMaxBalancedBatch ? c->max_batch : kMaxBalancedBatch;
+    const size_t balanced = balanced_slots(Bb, target);                 // >= B + workgroups of any balanced call
+    return best > balanced ? best : balanced;
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Carve {
-    size_t acc, ml, c, chat, total;
+    size_t acc, ml, seg, c, chat, total;
     size_t max_items;
     QProjPlan qproj;
     int32_t rows_pad;
@@ -83,6 +88,7 @@ Carve carve(const mfa_config* c, int32_t target)
     size_t off = 0;
     w.acc = off; off = align_up(off + w.max_items * kPartialAccFloats * sizeof(float), 256);
     w.ml = off;  off = align_up(off + w.max_items * kPartialMlFloats * sizeof(float), 256);
+    w.seg = off; off = align_up(off + (size_t)c->max_batch * 2 * sizeof(int32_t), 256);
     w.c = off;   off = align_up(off + (size_t)w.qproj.split_k * w.rows_pad * c->q_rank * sizeof(float), 256);
     w.chat = off; off = align_up(off + (size_t)w.rows_pad * c->q_rank * 2, 256);
     w.total = off;
@@ -122,6 +128,8 @@ void fill_common(const mfa_ctx* ctx, AttnArgs& a, int32_t B, int32_t hint)
     a.max_seq_len_hint = hint;
     a.ws_acc = ctx->ws_acc;
     a.ws_ml = ctx->ws_ml;
+    a.ws_seg = ctx->ws_seg;
+    a.n_wgs = ctx->fixed_splits ? 0 : balanced_workgroups(B, hint, ctx->target_items);
     a.scale_log2e = ctx->cfg.softmax_scale * 1.44269504088896340736f;
 }
 
@@ -160,10 +168,15 @@ mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t work
     if (!ctx) return MFA_ERR_INVALID_ARG;
     ctx->cfg = *cfg;
     ctx->target_items = target;
+    {
+        const char* sch = std::getenv("MFA_SCHEDULE");
+        ctx->fixed_splits = sch && std::string(sch) == "fixed";
+    }
     ctx->max_items = w.max_items;
     unsigned char* base = static_cast<unsigned char*>(d_workspace);
     ctx->ws_acc = reinterpret_cast<float*>(base + w.acc);
     ctx->ws_ml = reinterpret_cast<float*>(base + w.ml);
+    ctx->ws_seg = reinterpret_cast<int32_t*>(base + w.seg);
     ctx->ws_c = reinterpret_cast<float*>(base + w.c);
     ctx->ws_chat = base + w.chat;
     ctx->qproj = w.qproj;

@@ -33,6 +33,8 @@ constexpr int kAttnLdsBytes = 2 * kSlotBytes;         // bf16 kernel: 128 KB
 // fp8 kernel: two bf16 tile images, then per image 64 key scales and 64 value scales (fp32)
 constexpr int kFp8ScaleBase = 2 * kSlotBytes;
 constexpr int kFp8LdsBytes = 2 * kSlotBytes + 2 * 512;
+static_assert(kFp8LdsBytes <= kSchedLdsOffset && kAttnLdsBytes <= kSchedLdsOffset && kAttnLdsTotal <= 160 * 1024,
+              "the schedule's prefix sums live behind the tile memory of both kernels");
 
 // Page id of the tile that starts at token tile_t0 (paged cache only).  Looked up one tile ahead
 // of its use so that the table read is never on the critical path of issuing a tile's loads.
@@ -62,55 +64,59 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     const int n = lane & 15;
     const int g = lane >> 4;
 
-    const int item = blockIdx.x;
-    const ItemRange r = item_range(a, item);
-    if (r.t0 >= r.t1) { empty_item(a, r); return; }
+    Schedule sched = schedule_begin(a, lds_base);
+    Segment r;
+    bool first_segment = true;
+    while (schedule_next(a, lds_base, sched, r)) {
+        if (!first_segment) __syncthreads();          // the previous segment's exchange area is the tile memory
+        first_segment = false;
 
-    bf16x8 qf[8];
-    load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
+        bf16x8 qf[8];
+        load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
 
-    // Wave w brings rows [8w, 8w+8) of the tile's K and V: all in unit w/4.  Rows at or past t1
-    // re-read the last valid token, so nothing outside the sequence is touched and every LDS row
-    // holds finite data (the weights of those rows are masked to zero).
-    auto issue_tile = [&](int tile, int slot, int page) {
-        const int tile_t0 = r.t0 + tile * kTile;
-        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, page);
-        const int p16 = lane & 31;
+        // Wave w brings rows [8w, 8w+8) of the tile's K and V: all in unit w/4.  Rows at or past t1
+        // re-read the last valid token, so nothing outside the sequence is touched and every LDS row
+        // holds finite data (the weights of those rows are masked to zero).
+        auto issue_tile = [&](int tile, int slot, int page) {
+            const int tile_t0 = r.t0 + tile * kTile;
+            const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, page);
+            const int p16 = lane & 31;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int row = 8 * wave + 2 * u + (lane >> 5);          // row of the tile this lane fills
-            int in_tile = row;
-            if (tile_t0 + row > r.t1 - 1) in_tile = r.t1 - 1 - tile_t0;
-            const size_t grow = (size_t)(row0 + in_tile) * 512;
-            const int key = row & 15;
-            const int ck = p16 ^ key;
-            const int cv = ((((p16 >> 1) ^ key) << 1) | (p16 & 1));
-            const unsigned char* ksrc = (const unsigned char*)a.k + grow + ck * 16;
-            const unsigned char* vsrc = (const unsigned char*)a.v + grow + cv * 16;
-            const int first_row = 8 * wave + 2 * u;                   // wave-uniform
-            const uint32_t dst = lds_addr0 + slot * kSlotBytes + (first_row >> 5) * kUnitBytes + (first_row & 31) * 512;
-            load_to_lds_16B(ksrc, dst);
-            load_to_lds_16B(vsrc, dst + kUnitVOffset);
-        }
-    };
+            for (int u = 0; u < 4; ++u) {
+                const int row = 8 * wave + 2 * u + (lane >> 5);          // row of the tile this lane fills
+                int in_tile = row;
+                if (tile_t0 + row > r.t1 - 1) in_tile = r.t1 - 1 - tile_t0;
+                const size_t grow = (size_t)(row0 + in_tile) * 512;
+                const int key = row & 15;
+                const int ck = p16 ^ key;
+                const int cv = ((((p16 >> 1) ^ key) << 1) | (p16 & 1));
+                const unsigned char* ksrc = (const unsigned char*)a.k + grow + ck * 16;
+                const unsigned char* vsrc = (const unsigned char*)a.v + grow + cv * 16;
+                const int first_row = 8 * wave + 2 * u;                   // wave-uniform
+                const uint32_t dst = lds_addr0 + slot * kSlotBytes + (first_row >> 5) * kUnitBytes + (first_row & 31) * 512;
+                load_to_lds_16B(ksrc, dst);
+                load_to_lds_16B(vsrc, dst + kUnitVOffset);
+            }
+        };
 
-    WaveState st;
-    init_state(st);
+        WaveState st;
+        init_state(st);
 
-    issue_tile(0, 0, lookup_page<PAGED>(a, r.b, r.t0));
-    int page_next = r.n_tiles > 1 ? lookup_page<PAGED>(a, r.b, r.t0 + kTile) : 0;
-    for (int it = 0; it < r.n_tiles; ++it) {
-        const int slot = it & 1;
-        wait_vmem_all();
-        __syncthreads();
-        if (it + 1 < r.n_tiles) {
-            issue_tile(it + 1, slot ^ 1, page_next);
-            if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
+        issue_tile(0, 0, lookup_page<PAGED>(a, r.b, r.t0));
+        int page_next = r.n_tiles > 1 ? lookup_page<PAGED>(a, r.b, r.t0 + kTile) : 0;
+        for (int it = 0; it < r.n_tiles; ++it) {
+            const int slot = it & 1;
+            wait_vmem_all();
+            __syncthreads();
+            if (it + 1 < r.n_tiles) {
+                issue_tile(it + 1, slot ^ 1, page_next);
+                if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
+            }
+            process_unit<false>(st, qf, lds_base, slot * kSlotBytes + grp * kUnitBytes,
+                                r.t0 + it * kTile + grp * kUnitTokens, r.t1, a.scale_log2e, n, g, 0, 0);
         }
-        process_unit<false>(st, qf, lds_base, slot * kSlotBytes + grp * kUnitBytes,
-                            r.t0 + it * kTile + grp * kUnitTokens, r.t1, a.scale_log2e, n, g, 0, 0);
+        finish_segment(st, lds_base, a, r, wq, grp, lane);
     }
-    finish_item(st, lds_base, a, r.b, item, wq, grp, lane);
 }
 
 // One tile of fp8 codes held in registers on its way from HBM to the bf16 LDS image: the
@@ -142,6 +148,15 @@ __device__ __forceinline__ void wait_tile_older_of_two(Fp8TileRegs& t)
                  : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.piece[2]), "+v"(t.piece[3]), "+v"(t.scale) :: "memory");
 }
 
+// Wait for every load in flight while both register sets are still owned by the pipeline: no
+// register of theirs may be handed to other code before its load has landed.
+__device__ __forceinline__ void drain_tiles(Fp8TileRegs& t, Fp8TileRegs& u)
+{
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.piece[2]), "+v"(t.piece[3]), "+v"(t.scale),
+                   "+v"(u.piece[0]), "+v"(u.piece[1]), "+v"(u.piece[2]), "+v"(u.piece[3]), "+v"(u.scale) :: "memory");
+}
+
 template <bool PAGED>
 __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
 {
@@ -155,106 +170,112 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
     const int n = lane & 15;
     const int g = lane >> 4;
 
-    const int item = blockIdx.x;
-    const ItemRange r = item_range(a, item);
-    if (r.t0 >= r.t1) { empty_item(a, r); return; }
+    Schedule sched = schedule_begin(a, lds_base);
+    Segment r;
+    bool first_segment = true;
+    while (schedule_next(a, lds_base, sched, r)) {
+        if (!first_segment) __syncthreads();          // the previous segment's exchange area is the tile memory
+        first_segment = false;
 
-    // Piece i of this thread: tensor (i >> 1 ? V : K), row (threadIdx.x >> 4) + 32*(i & 1), 16-byte
-    // chunk threadIdx.x & 15, so that consecutive threads read consecutive 16 bytes.  Rows at or
-    // past t1 re-read the last valid token.
-    const int prow = threadIdx.x >> 4;
-    const int pchunk = threadIdx.x & 15;
-    auto load_tile = [&](Fp8TileRegs& t, int tile) {
-        if (tile >= r.n_tiles) tile = r.n_tiles - 1;   // past the end: re-read the last tile (never consumed)
-        const int tile_t0 = r.t0 + tile * kTile;
-        const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, lookup_page<PAGED>(a, r.b, tile_t0));
-        const int last = r.t1 - 1 - tile_t0;                          // last valid row of this tile (>= 0)
+        // Piece i of this thread: tensor (i >> 1 ? V : K), row (threadIdx.x >> 4) + 32*(i & 1), 16-byte
+        // chunk threadIdx.x & 15, so that consecutive threads read consecutive 16 bytes.  Rows at or
+        // past t1 re-read the last valid token.
+        const int prow = threadIdx.x >> 4;
+        const int pchunk = threadIdx.x & 15;
+        auto load_tile = [&](Fp8TileRegs& t, int tile) {
+            if (tile >= r.n_tiles) tile = r.n_tiles - 1;   // past the end: re-read the last tile (never consumed)
+            const int tile_t0 = r.t0 + tile * kTile;
+            const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, lookup_page<PAGED>(a, r.b, tile_t0));
+            const int last = r.t1 - 1 - tile_t0;                          // last valid row of this tile (>= 0)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = prow + 32 * (i & 1);
-            const int in_tile = row > last ? last : row;
-            const unsigned char* base = (const unsigned char*)((i >> 1) ? a.v : a.k);
-            load_regs_16B(t.piece[i], base + (size_t)(row0 + in_tile) * 256 + pchunk * 16);
-        }
-        {
-            // every thread loads a scale (threads 128.. repeat those of 0..127) so that the loads of a
-            // tile form one straight-line group: the wait for an older tile can then leave the newer
-            // tile's loads in flight
-            const int tok = threadIdx.x & 63;
-            const int in_tile = tok > last ? last : tok;
-            load_regs_4B(t.scale, ((threadIdx.x & 64) ? a.v_scale : a.k_scale) + (row0 + in_tile));
-        }
-    };
-
-    // Convert a tile's codes to bf16 (exact: every e4m3 value is a bf16 value) and write them into
-    // image `slot` in the swizzled unit layout; the scales go beside it.
-    auto store_tile = [&](const Fp8TileRegs& t, int slot) {
-        const int image = slot * kSlotBytes;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            bf16x8 half[2];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], false);
-                const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], true);
-                half[w >> 1][4 * (w & 1) + 0] = (__bf16)f01[0];
-                half[w >> 1][4 * (w & 1) + 1] = (__bf16)f01[1];
-                half[w >> 1][4 * (w & 1) + 2] = (__bf16)f23[0];
-                half[w >> 1][4 * (w & 1) + 3] = (__bf16)f23[1];
+            for (int i = 0; i < 4; ++i) {
+                const int row = prow + 32 * (i & 1);
+                const int in_tile = row > last ? last : row;
+                const unsigned char* base = (const unsigned char*)((i >> 1) ? a.v : a.k);
+                load_regs_16B(t.piece[i], base + (size_t)(row0 + in_tile) * 256 + pchunk * 16);
             }
-            const int key = prow & 15;                                 // row within its unit = prow (0..31)
-            const int unit = image + (i & 1) * kUnitBytes + prow * 512;
-            if (i >> 1) {
-                const int off = unit + kUnitVOffset + ((pchunk ^ key) << 5);
-                *LDS_AT(bf16x8, lds_base, off) = half[0];
-                *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
-            } else {
-                *LDS_AT(bf16x8, lds_base, unit + (((2 * pchunk) ^ key) << 4)) = half[0];
-                *LDS_AT(bf16x8, lds_base, unit + (((2 * pchunk + 1) ^ key) << 4)) = half[1];
+            {
+                // every thread loads a scale (threads 128.. repeat those of 0..127) so that the loads of a
+                // tile form one straight-line group: the wait for an older tile can then leave the newer
+                // tile's loads in flight
+                const int tok = threadIdx.x & 63;
+                const int in_tile = tok > last ? last : tok;
+                load_regs_4B(t.scale, ((threadIdx.x & 64) ? a.v_scale : a.k_scale) + (row0 + in_tile));
             }
+        };
+
+        // Convert a tile's codes to bf16 (exact: every e4m3 value is a bf16 value) and write them into
+        // image `slot` in the swizzled unit layout; the scales go beside it.
+        auto store_tile = [&](const Fp8TileRegs& t, int slot) {
+            const int image = slot * kSlotBytes;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                bf16x8 half[2];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], false);
+                    const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], true);
+                    half[w >> 1][4 * (w & 1) + 0] = (__bf16)f01[0];
+                    half[w >> 1][4 * (w & 1) + 1] = (__bf16)f01[1];
+                    half[w >> 1][4 * (w & 1) + 2] = (__bf16)f23[0];
+                    half[w >> 1][4 * (w & 1) + 3] = (__bf16)f23[1];
+                }
+                const int key = prow & 15;                                 // row within its unit = prow (0..31)
+                const int unit = image + (i & 1) * kUnitBytes + prow * 512;
+                if (i >> 1) {
+                    const int off = unit + kUnitVOffset + ((pchunk ^ key) << 5);
+                    *LDS_AT(bf16x8, lds_base, off) = half[0];
+                    *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
+                } else {
+                    *LDS_AT(bf16x8, lds_base, unit + (((2 * pchunk) ^ key) << 4)) = half[0];
+                    *LDS_AT(bf16x8, lds_base, unit + (((2 * pchunk + 1) ^ key) << 4)) = half[1];
+                }
+            }
+            if (threadIdx.x < 128) *LDS_AT(float, lds_base, kFp8ScaleBase + slot * 512 + threadIdx.x * 4) = t.scale;
+        };
+
+        WaveState st;
+        init_state(st);
+
+        // Pipeline: tile t+2 (and t+3) travel from HBM to registers while tile t+1 is converted into the
+        // other LDS image and tile t is consumed from its image; one barrier per tile.
+        Fp8TileRegs regs[2];
+        // The loads of every step are issued unconditionally (clamped to the last tile) so that exactly
+        // two tiles' loads are outstanding whenever one is awaited.
+        load_tile(regs[0], 0);
+        load_tile(regs[1], 1);
+        // The query fragments are loaded by ordinary loads and pinned here: the compiler completes them
+        // (and with them the two tiles above) before the loop, instead of waiting for them, and so for
+        // every load in flight, inside it.
+        bf16x8 qf[8];
+        load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
+        asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7]));
+        wait_tile_older_of_two(regs[0]);
+        store_tile(regs[0], 0);
+        load_tile(regs[0], 2);
+
+        auto step = [&](auto parity_c, int t) {
+            constexpr int P = decltype(parity_c)::value;                    // t & 1
+            __syncthreads();              // image P holds tile t; everyone is done with image P^1 (tile t-1)
+            wait_tile_older_of_two(regs[P ^ 1]);
+            store_tile(regs[P ^ 1], P ^ 1);                                 // tile t+1 (a repeat of the last tile at the end)
+            load_tile(regs[P ^ 1], t + 3);
+            const int scales = kFp8ScaleBase + P * 512 + grp * kUnitTokens * 4;
+            process_unit<true>(st, qf, lds_base, P * kSlotBytes + grp * kUnitBytes, r.t0 + t * kTile + grp * kUnitTokens,
+                               r.t1, a.scale_log2e, n, g, scales, scales + 256);
+        };
+        for (int t = 0; t < r.n_tiles; t += 2) {
+            step(std::integral_constant<int, 0>{}, t);
+            if (t + 1 >= r.n_tiles) break;
+            step(std::integral_constant<int, 1>{}, t + 1);
         }
-        if (threadIdx.x < 128) *LDS_AT(float, lds_base, kFp8ScaleBase + slot * 512 + threadIdx.x * 4) = t.scale;
-    };
-
-    WaveState st;
-    init_state(st);
-
-    // Pipeline: tile t+2 (and t+3) travel from HBM to registers while tile t+1 is converted into the
-    // other LDS image and tile t is consumed from its image; one barrier per tile.
-    Fp8TileRegs regs[2];
-    // The loads of every step are issued unconditionally (clamped to the last tile) so that exactly
-    // two tiles' loads are outstanding whenever one is awaited.
-    load_tile(regs[0], 0);
-    load_tile(regs[1], 1);
-    // The query fragments are loaded by ordinary loads and pinned here: the compiler completes them
-    // (and with them the two tiles above) before the loop, instead of waiting for them, and so for
-    // every load in flight, inside it.
-    bf16x8 qf[8];
-    load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
-    asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7]));
-    wait_tile_older_of_two(regs[0]);
-    store_tile(regs[0], 0);
-    load_tile(regs[0], 2);
-
-    auto step = [&](auto parity_c, int t) {
-        constexpr int P = decltype(parity_c)::value;                    // t & 1
-        __syncthreads();              // image P holds tile t; everyone is done with image P^1 (tile t-1)
-        wait_tile_older_of_two(regs[P ^ 1]);
-        store_tile(regs[P ^ 1], P ^ 1);                                 // tile t+1 (a repeat of the last tile at the end)
-        load_tile(regs[P ^ 1], t + 3);
-        const int scales = kFp8ScaleBase + P * 512 + grp * kUnitTokens * 4;
-        process_unit<true>(st, qf, lds_base, P * kSlotBytes + grp * kUnitBytes, r.t0 + t * kTile + grp * kUnitTokens,
-                           r.t1, a.scale_log2e, n, g, scales, scales + 256);
-    };
-    for (int t = 0; t < r.n_tiles; t += 2) {
-        step(std::integral_constant<int, 0>{}, t);
-        if (t + 1 >= r.n_tiles) break;
-        step(std::integral_constant<int, 1>{}, t + 1);
+        drain_tiles(regs[0], regs[1]);        // the repeats of the last tile issued past the end
+        finish_segment(st, lds_base, a, r, wq, grp, lane);
     }
-    finish_item(st, lds_base, a, r.b, item, wq, grp, lane);
 }
 
-// Merge the partial results of the splits of one sequence:
+// Merge the partial results of one sequence (fixed splits: slots b*n_splits ...; balanced schedule:
+// the slots recorded by the workgroup that held the sequence's first tile):
 //   out = sum_s 2^(m_s - m*) acc_s / sum_s 2^(m_s - m*) l_s,  m* = max_s m_s,
 // summed in split order.  One thread per float4 of the partial's lane-order layout; splits are
 // taken four at a time so that their loads are independent and in flight together.
@@ -271,9 +292,19 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
     const int d = 16 * db + 4 * (lane >> 4);
     int L = a.seq_lens[b];
     L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
-    if (L == 0) return;                                               // zeros were written by the first item
-    const int n_valid = (L + a.chunk_tokens - 1) / a.chunk_tokens;    // <= n_splits
-    const size_t item0 = (size_t)b * a.n_splits;
+    float4* const o = (float4*)(a.out + ((size_t)b * kHeads + h) * kHeadDim + d);
+    int n_valid;
+    size_t item0;
+    if (a.n_wgs > 0) {                                                // balanced schedule
+        if (L == 0) { *o = make_float4(0.f, 0.f, 0.f, 0.f); return; }
+        item0 = (size_t)a.ws_seg[2 * b];
+        n_valid = a.ws_seg[2 * b + 1];
+        if (n_valid == 1) return;                                     // one workgroup held it all and wrote the result
+    } else {
+        if (L == 0) return;                                           // zeros were written by the first split
+        n_valid = (L + a.chunk_tokens - 1) / a.chunk_tokens;          // <= n_splits
+        item0 = (size_t)b * a.n_splits;
+    }
     const float2* ml_base = (const float2*)a.ws_ml + item0 * kHeads + h;
     const float4* acc_base = (const float4*)a.ws_acc + item0 * (kHeads * kHeadDim / 4) + p;
 
@@ -307,8 +338,7 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
         }
     }
     const float inv = 1.0f / l;
-    *(float4*)(a.out + ((size_t)b * kHeads + h) * kHeadDim + d) =
-        make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
+    *o = make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
 }
 
 // Copy the logical rows of every sequence out of a paged pool (test aid).
@@ -368,38 +398,46 @@ SplitPlan plan_splits(int32_t B, int32_t max_seq_len_hint, int32_t target_items)
     return p;
 }
 
+int32_t balanced_workgroups(int32_t B, int32_t max_seq_len_hint, int32_t target_items)
+{
+    if (B > kMaxBalancedBatch) return 0;
+    const int64_t max_tiles = (int64_t)B * ((max_seq_len_hint + kTile - 1) / kTile);
+    return (int32_t)(max_tiles < target_items ? max_tiles : target_items);
+}
+
 hipError_t prepare_decode_attn_kernels()
 {
     hipError_t e;
-    e = hipFuncSetAttribute((const void*)decode_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes);
+    e = hipFuncSetAttribute((const void*)decode_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)decode_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes);
+    e = hipFuncSetAttribute((const void*)decode_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)decode_fp8_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kFp8LdsBytes);
+    e = hipFuncSetAttribute((const void*)decode_fp8_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)decode_fp8_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kFp8LdsBytes);
+    e = hipFuncSetAttribute((const void*)decode_fp8_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
     return e;
 }
 
 hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream,
                               hipEvent_t ev_before, hipEvent_t ev_after)
 {
-    const dim3 grid((unsigned)(a.B * a.n_splits));
+    const dim3 grid((unsigned)(a.n_wgs > 0 ? a.n_wgs : a.B * a.n_splits));
     const dim3 block(kAttnThreads);
     if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return hipErrorNotSupported;
     // The two events, when given, are attached to the streaming kernel's own dispatch: they take the
     // times at which that kernel starts and ends on the device, with no launch gap inside the interval.
     if (!(ev_before && ev_after)) ev_before = ev_after = nullptr;
+    const unsigned kAttnLdsTotal_ = a.n_wgs > 0 ? kAttnLdsTotal : kSchedLdsOffset;   // the schedule's arrays only if used
     if (kv_dtype == MFA_KV_BF16) {
-        if (a.block_table) hipExtLaunchKernelGGL(decode_bf16_kernel<true>, grid, block, kAttnLdsBytes, stream, ev_before, ev_after, 0, a);
-        else               hipExtLaunchKernelGGL(decode_bf16_kernel<false>, grid, block, kAttnLdsBytes, stream, ev_before, ev_after, 0, a);
+        if (a.block_table) hipExtLaunchKernelGGL(decode_bf16_kernel<true>, grid, block, kAttnLdsTotal_, stream, ev_before, ev_after, 0, a);
+        else               hipExtLaunchKernelGGL(decode_bf16_kernel<false>, grid, block, kAttnLdsTotal_, stream, ev_before, ev_after, 0, a);
     } else {
-        if (a.block_table) hipExtLaunchKernelGGL(decode_fp8_kernel<true>, grid, block, kFp8LdsBytes, stream, ev_before, ev_after, 0, a);
-        else               hipExtLaunchKernelGGL(decode_fp8_kernel<false>, grid, block, kFp8LdsBytes, stream, ev_before, ev_after, 0, a);
+        if (a.block_table) hipExtLaunchKernelGGL(decode_fp8_kernel<true>, grid, block, kAttnLdsTotal_, stream, ev_before, ev_after, 0, a);
+        else               hipExtLaunchKernelGGL(decode_fp8_kernel<false>, grid, block, kAttnLdsTotal_, stream, ev_before, ev_after, 0, a);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (a.n_splits > 1) {
+    if (a.n_wgs > 0 || a.n_splits > 1) {
         const unsigned blocks = (unsigned)(((size_t)a.B * kHeads * (kHeadDim / 4) + 255) / 256);
         hipLaunchKernelGGL(merge_splits_kernel, dim3(blocks), dim3(256), 0, stream, a);
         e = hipGetLastError();

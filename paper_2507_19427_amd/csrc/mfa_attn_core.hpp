@@ -199,8 +199,8 @@ __device__ __forceinline__ void process_unit(WaveState& st, const bf16x8 (&qf)[8
 // result goes to `out`.  Several splits: the unnormalised partial goes to the workspace in
 // lane order (float4 index (wq*16 + db)*64 + lane, fully coalesced), with (m, l) per head.
 template <int KEEP, int SEND>
-__device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, int b, int item,
-                                            int wq, int grp, int lane)
+__device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, int b, int slot,
+                                            bool final_result, int wq, int grp, int lane)
 {
     const int n = lane & 15, g = lane >> 4;
     const int head = 16 * wq + n;
@@ -214,14 +214,13 @@ __device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, c
     __syncthreads();
     const float m_o = *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + (grp ^ 1)) * 2 + 0) * 256 + lane * 4);
     const float l_o = *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + (grp ^ 1)) * 2 + 1) * 256 + lane * 4);
-    const float m = fmaxf(st.m, m_o);                 // finite: the item has a token, seen by grp 0
+    const float m = fmaxf(st.m, m_o);                 // finite: the segment has a token, seen by grp 0
     const float w_s = fast_exp2(st.m - m);
     const float w_o = fast_exp2(m_o - m);
     const float l = st.l * w_s + l_o * w_o;
     const float inv = 1.0f / l;
-    const bool final_result = a.n_splits == 1;
     float* o = a.out + ((size_t)b * kHeads + head) * kHeadDim + 4 * g;
-    f32x4* part = (f32x4*)a.ws_acc + (size_t)item * (kHeads * kHeadDim / 4) + (size_t)wq * 16 * 64 + lane;
+    f32x4* part = (f32x4*)a.ws_acc + (size_t)slot * (kHeads * kHeadDim / 4) + (size_t)wq * 16 * 64 + lane;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const f32x4 other = *LDS_AT(f32x4, lds_base, (theirs + i) * 1024 + lane * 16);
@@ -230,42 +229,265 @@ __device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, c
         else part[(KEEP + i) * 64] = r;
     }
     if (!final_result && grp == 0 && g == 0)
-        *(float2*)(a.ws_ml + ((size_t)item * kHeads + head) * 2) = make_float2(m, l);
+        *(float2*)(a.ws_ml + ((size_t)slot * kHeads + head) * 2) = make_float2(m, l);
 }
 
-__device__ __forceinline__ void finish_item(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, int b, int item,
-                                            int wq, int grp, int lane)
+// One piece of work: tokens [t0, t1) of sequence b (n_tiles tiles of 64, the last one possibly
+// ragged).  Its result is the sequence's final output (final_result) or a partial in `slot`.
+struct Segment {
+    int b, t0, t1, n_tiles, slot;
+    bool final_result;
+};
+
+// Every field of a segment is the same in all threads; saying so keeps the branches on them scalar.
+__device__ __forceinline__ void make_uniform(Segment& r)
+{
+    r.b = __builtin_amdgcn_readfirstlane(r.b);
+    r.t0 = __builtin_amdgcn_readfirstlane(r.t0);
+    r.t1 = __builtin_amdgcn_readfirstlane(r.t1);
+    r.n_tiles = __builtin_amdgcn_readfirstlane(r.n_tiles);
+    r.slot = __builtin_amdgcn_readfirstlane(r.slot);
+    r.final_result = __builtin_amdgcn_readfirstlane((int)r.final_result) != 0;
+}
+
+__device__ __forceinline__ void finish_segment(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, const Segment& r,
+                                               int wq, int grp, int lane)
 {
     st.l = head_sum(st.l);
     __syncthreads();                                  // every wave is done reading the tile buffers
-    if (grp == 0) finish_half<0, 8>(st, lds_base, a, b, item, wq, grp, lane);
-    else          finish_half<8, 0>(st, lds_base, a, b, item, wq, grp, lane);
+    if (grp == 0) finish_half<0, 8>(st, lds_base, a, r.b, r.slot, r.final_result, wq, grp, lane);
+    else          finish_half<8, 0>(st, lds_base, a, r.b, r.slot, r.final_result, wq, grp, lane);
 }
 
-// Work item bookkeeping common to both kernels.
-struct ItemRange {
-    int b, split, t0, t1, n_tiles;
+__device__ __forceinline__ int clamped_len(const AttnArgs& a, int b)
+{
+    const int L = a.seq_lens[b];
+    return L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
+}
+
+// ---- Which segments a workgroup works off.
+//
+// Fixed splits (n_wgs == 0): workgroup = (sequence, split), one segment of chunk_tokens tokens;
+// the partial slot is the workgroup index; the first split of an empty sequence writes the zeros.
+//
+// Balanced (n_wgs > 0): with T_b = ceil(L_b / 64) tiles per sequence and P the exclusive prefix
+// sums of T, workgroup w takes the tile range [w*N/G, (w+1)*N/G) of the N = P[B] tiles laid end to
+// end (G = min(n_wgs, N), so that no workgroup below G is idle) and cuts it at sequence boundaries.  The workgroups touching sequence b are
+// consecutive, first(b)..last(b) with wg_of(t) = ((t+1)*G - 1) / N; the segment of workgroup w on
+// sequence b uses partial slot w + b, which is unique because (w, b) grows in at least one
+// coordinate from one segment to the next, and the slots of one sequence are consecutive.  The
+// workgroup holding a sequence's first tile records (first slot, number of partials) for the
+// merge; a sequence held by one workgroup is written finally and needs no merge.  Sequences
+// without tokens are zero-filled by the merge kernel.
+constexpr int kSchedLdsOffset = 2 * 2 * kUnitBytes + 1024;                // behind both kernels' tile memory
+constexpr int kSchedTotalsOffset = kSchedLdsOffset + (kMaxBalancedBatch + 1) * 4 + 12;   // 8 wave totals
+constexpr int kSchedFoundOffset = kSchedTotalsOffset + 8 * 4;                           // result of the search
+constexpr int kSchedRemOffset = kSchedFoundOffset + 16;     // per sequence: tokens in its last tile, minus one (a byte)
+constexpr int kSchedLdsBytes = kSchedRemOffset + kMaxBalancedBatch - kSchedLdsOffset;
+constexpr int kAttnLdsTotal = kSchedLdsOffset + kSchedLdsBytes;
+
+struct Schedule {
+    int lo, hi;         // balanced: my tile range; fixed: hi > lo while my one segment is still to do
+    int n_tiles_all;    // N
+    int n_wgs;          // G: workgroups that have a range (min of the grid size and N)
+    int my_lo;          // start of my range (lo moves on as segments are handed out)
+    bool first_known;   // the first segment's sequence is described below (no table lookup needed)
+    int first_seq0, first_seq1, first_len;
+    int b;              // next sequence to look at
 };
-__device__ __forceinline__ ItemRange item_range(const AttnArgs& a, int item)
+
+// floor(x * N / G) and the workgroup of a tile, in 32 bits when the products fit.
+__device__ __forceinline__ int scaled_floor(int x, int N, int G)
 {
-    ItemRange r;
-    r.b = item / a.n_splits;
-    r.split = item - r.b * a.n_splits;
-    int L = a.seq_lens[r.b];
-    L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
-    r.t0 = r.split * a.chunk_tokens;
-    r.t1 = (r.t0 + a.chunk_tokens < L) ? r.t0 + a.chunk_tokens : L;
-    r.n_tiles = (r.t1 - r.t0 + kTile - 1) / kTile;
-    return r;
+    if (N < (1 << 20) && x <= (1 << 11)) return (int)((unsigned)x * (unsigned)N / (unsigned)G);
+    return (int)((unsigned long long)x * (unsigned long long)N / (unsigned long long)G);
+}
+__device__ __forceinline__ int wg_of_tile(int t, int G, int N)
+{
+    if (N < (1 << 20) && G <= (1 << 11)) return (int)((((unsigned)t + 1u) * (unsigned)G - 1u) / (unsigned)N);
+    return (int)((((unsigned long long)t + 1ull) * (unsigned long long)G - 1ull) / (unsigned long long)N);
 }
 
-// An item without tokens: the first item of an empty sequence writes the zero result.
-__device__ __forceinline__ void empty_item(const AttnArgs& a, const ItemRange& r)
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add 0), then lane 15 of rows 0 and
+// 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int wave_inclusive_scan(int v)
 {
-    if (r.split == 0) {
-        float4* o = (float4*)(a.out + (size_t)r.b * kHeads * kHeadDim);
-        for (int i = threadIdx.x; i < kHeads * kHeadDim / 4; i += kAttnThreads) o[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);    // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);    // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);    // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);    // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);    // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);    // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+// All threads of the workgroup call this; the values returned are the same in every thread.
+//
+// Batches of up to 512 sequences: every wave scans the whole batch by itself (eight lengths per
+// lane at most), so the way to a workgroup's first segment crosses no barrier and no LDS; wave 0
+// also leaves the tables in LDS for the later segments, which are requested only after the
+// barriers of the first one.  Larger batches: one cooperative scan through LDS.
+constexpr int kWaveScanChunks = 8;
+__device__ __forceinline__ Schedule schedule_begin(const AttnArgs& a, lds_ptr_t lds_base)
+{
+    Schedule s;
+    s.first_known = false;
+    s.first_seq0 = s.first_seq1 = s.first_len = 0;
+    if (a.n_wgs == 0) { s.lo = s.my_lo = 0; s.hi = 1; s.n_tiles_all = 0; s.n_wgs = 0; s.b = 0; return s; }
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+
+    if (a.B <= kWaveScanChunks * 64) {
+        int len[kWaveScanChunks], p1[kWaveScanChunks];
+#pragma unroll
+        for (int c = 0; c < kWaveScanChunks; ++c) {
+            const int i = c * 64 + lane;
+            len[c] = (c * 64 < a.B && i < a.B) ? clamped_len(a, i) : 0;
+        }
+        int N = 0;
+#pragma unroll
+        for (int c = 0; c < kWaveScanChunks; ++c) {
+            p1[c] = N;
+            if (c * 64 < a.B) {
+                const int incl = wave_inclusive_scan((len[c] + kTile - 1) / kTile);
+                p1[c] = N + incl;                                      // P[i + 1]
+                N += __builtin_amdgcn_readlane(incl, 63);
+            }
+        }
+        if (wave == 0) {
+            if (lane == 0) *LDS_AT(int, lds_base, kSchedLdsOffset) = 0;
+#pragma unroll
+            for (int c = 0; c < kWaveScanChunks; ++c) {
+                const int i = c * 64 + lane;
+                if (i < a.B) {
+                    *LDS_AT(int, lds_base, kSchedLdsOffset + (i + 1) * 4) = p1[c];
+                    *LDS_AT(unsigned char, lds_base, kSchedRemOffset + i) = (unsigned char)((len[c] - 1) & (kTile - 1));
+                }
+            }
+        }
+        const int G = a.n_wgs < N ? a.n_wgs : N;      // with fewer tiles than workgroups the last ones idle
+        s.n_tiles_all = N;
+        s.n_wgs = G;
+        if ((int)blockIdx.x >= G) { s.lo = s.hi = s.b = s.my_lo = 0; return s; }
+        s.lo = s.my_lo = __builtin_amdgcn_readfirstlane(scaled_floor((int)blockIdx.x, N, G));
+        s.hi = __builtin_amdgcn_readfirstlane(scaled_floor((int)blockIdx.x + 1, N, G));
+        s.b = 0;
+#pragma unroll
+        for (int c = 0; c < kWaveScanChunks; ++c) {
+            const int x = (len[c] + kTile - 1) / kTile;
+            const unsigned long long hit = __ballot(p1[c] - x <= s.lo && s.lo < p1[c]);   // at most one lane of one chunk
+            if (hit) {
+                const int src = __builtin_amdgcn_readfirstlane(__builtin_ctzll(hit));
+                s.b = c * 64 + src;
+                s.first_seq1 = __builtin_amdgcn_readlane(p1[c], src);
+                s.first_seq0 = s.first_seq1 - __builtin_amdgcn_readlane(x, src);
+                s.first_len = __builtin_amdgcn_readlane(len[c], src);
+                s.first_known = true;
+            }
+        }
+        return s;
     }
+
+    constexpr int totals = kSchedTotalsOffset;
+    constexpr int found = kSchedFoundOffset;
+    if (threadIdx.x == 0) *LDS_AT(int, lds_base, kSchedLdsOffset) = 0;
+    int carry = 0;
+    for (int base = 0; base < a.B; base += kAttnThreads) {
+        const int i = base + threadIdx.x;
+        const int len = i < a.B ? clamped_len(a, i) : 0;
+        const int x = (len + kTile - 1) / kTile;
+        if (i < a.B) *LDS_AT(unsigned char, lds_base, kSchedRemOffset + i) = (unsigned char)((len - 1) & (kTile - 1));
+        const int incl = wave_inclusive_scan(x);
+        if (lane == 63) *LDS_AT(int, lds_base, totals + wave * 4) = incl;
+        __syncthreads();
+        int before = carry, all = 0;
+#pragma unroll
+        for (int w = 0; w < kAttnThreads / 64; ++w) {
+            const int tw = *LDS_AT(int, lds_base, totals + w * 4);
+            all += tw;
+            if (w < wave) before += tw;
+        }
+        if (i < a.B) *LDS_AT(int, lds_base, kSchedLdsOffset + (i + 1) * 4) = before + incl;    // P[i + 1]
+        carry += all;
+        __syncthreads();
+    }
+    const int N = carry;
+    const int G = a.n_wgs < N ? a.n_wgs : N;
+    s.n_tiles_all = __builtin_amdgcn_readfirstlane(N);
+    s.n_wgs = __builtin_amdgcn_readfirstlane(G);
+    if ((int)blockIdx.x >= G) { s.lo = s.hi = s.b = s.my_lo = 0; return s; }
+    s.lo = s.my_lo = __builtin_amdgcn_readfirstlane(scaled_floor((int)blockIdx.x, N, G));
+    s.hi = __builtin_amdgcn_readfirstlane(scaled_floor((int)blockIdx.x + 1, N, G));
+    for (int base = 0; base < a.B; base += kAttnThreads) {
+        const int i = base + threadIdx.x;
+        if (i < a.B) {
+            const int p0 = *LDS_AT(int, lds_base, kSchedLdsOffset + i * 4);
+            const int p1 = *LDS_AT(int, lds_base, kSchedLdsOffset + (i + 1) * 4);
+            if (p0 <= s.lo && s.lo < p1) *LDS_AT(int, lds_base, found) = i;
+        }
+    }
+    __syncthreads();
+    s.b = __builtin_amdgcn_readfirstlane(*LDS_AT(int, lds_base, found));   // the one sequence with P[b] <= lo < P[b + 1]
+    return s;
+}
+
+// The next segment of this workgroup, or false when it has none left.  A false return for the very
+// first request of a fixed-split workgroup on an empty sequence has written the zero result.
+__device__ __forceinline__ bool schedule_next(const AttnArgs& a, lds_ptr_t lds_base, Schedule& s, Segment& r)
+{
+    if (s.lo >= s.hi) return false;
+    if (a.n_wgs == 0) {
+        s.hi = 0;
+        const int item = blockIdx.x;
+        r.b = item / a.n_splits;
+        const int split = item - r.b * a.n_splits;
+        const int L = clamped_len(a, r.b);
+        r.t0 = split * a.chunk_tokens;
+        r.t1 = (r.t0 + a.chunk_tokens < L) ? r.t0 + a.chunk_tokens : L;
+        r.n_tiles = (r.t1 - r.t0 + kTile - 1) / kTile;
+        r.slot = item;
+        r.final_result = a.n_splits == 1;
+        if (r.t0 >= r.t1) {
+            if (split == 0) {
+                float4* o = (float4*)(a.out + (size_t)r.b * kHeads * kHeadDim);
+                for (int i = threadIdx.x; i < kHeads * kHeadDim / 4; i += kAttnThreads) o[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            return false;
+        }
+        make_uniform(r);
+        return true;
+    }
+    int b = s.b, seq0, seq1, L;
+    if (s.first_known) {
+        s.first_known = false;
+        seq0 = s.first_seq0; seq1 = s.first_seq1; L = s.first_len;
+    } else {
+        while (*LDS_AT(int, lds_base, kSchedLdsOffset + (b + 1) * 4) <= s.lo) ++b;     // sequences without tiles
+        seq0 = __builtin_amdgcn_readfirstlane(*LDS_AT(int, lds_base, kSchedLdsOffset + b * 4));
+        seq1 = __builtin_amdgcn_readfirstlane(*LDS_AT(int, lds_base, kSchedLdsOffset + (b + 1) * 4));
+        b = __builtin_amdgcn_readfirstlane(b);
+        const int rem = __builtin_amdgcn_readfirstlane((int)*LDS_AT(unsigned char, lds_base, kSchedRemOffset + b));
+        L = (seq1 - seq0 - 1) * kTile + rem + 1;                      // the sequence's (clamped) length
+    }
+    const int end = s.hi < seq1 ? s.hi : seq1;
+    r.b = b;
+    r.t0 = (s.lo - seq0) * kTile;
+    r.t1 = (end - seq0) * kTile < L ? (end - seq0) * kTile : L;
+    r.n_tiles = end - s.lo;
+    r.final_result = seq0 >= s.my_lo && seq1 <= s.hi;                // the whole sequence lies in my range
+    r.slot = (int)blockIdx.x + b;
+    if (s.lo == seq0) {                                               // I hold its first tile: tell the merge
+        const int last = r.final_result ? (int)blockIdx.x : wg_of_tile(seq1 - 1, s.n_wgs, s.n_tiles_all);
+        if (threadIdx.x == 0) {
+            a.ws_seg[2 * b] = (int)blockIdx.x + b;
+            a.ws_seg[2 * b + 1] = last - (int)blockIdx.x + 1;
+        }
+    }
+    s.lo = end;
+    s.b = b + 1;
+    make_uniform(r);
+    return true;
 }
 
 }  // namespace mfa

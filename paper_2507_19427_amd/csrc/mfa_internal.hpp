@@ -24,6 +24,14 @@ struct SplitPlan {
 };
 SplitPlan plan_splits(int32_t B, int32_t max_seq_len_hint, int32_t target_items);
 
+// Balanced schedule (batches of at most kMaxBalancedBatch sequences): the tiles of all sequences,
+// laid end to end in sequence order, are cut into n_wgs equal ranges, one per workgroup; a range
+// that crosses sequence boundaries is worked off as one segment per sequence.  The workgroup
+// count, and the number of partial-result slots that any schedule over it can need.
+constexpr int32_t kMaxBalancedBatch = 4096;
+int32_t balanced_workgroups(int32_t B, int32_t max_seq_len_hint, int32_t target_items);   // 0 if B is too large
+inline size_t balanced_slots(int32_t B, int32_t n_wgs) { return (size_t)B + (size_t)n_wgs; }
+
 // Per work item the split kernel leaves: acc [kHeads][kHeadDim] fp32 (unnormalised),
 // and (m, l) per head: running maximum in the log2 domain and the sum of weights.
 constexpr size_t kPartialAccFloats = (size_t)kHeads * kHeadDim;
@@ -40,9 +48,11 @@ struct AttnArgs {
     float* out;                    // fp32 [B,64,256]
     float* ws_acc;                 // [B*n_splits][64][256]
     float* ws_ml;                  // [B*n_splits][64][2]
+    int32_t* ws_seg;               // balanced schedule: per sequence (first partial slot, number of partials)
     int64_t seq_stride_tokens;     // contiguous only
     int32_t max_blocks_per_seq;    // paged only
     int32_t B;
+    int32_t n_wgs;                 // > 0: balanced schedule over this many workgroups; 0: fixed splits below
     int32_t n_splits;
     int32_t chunk_tokens;
     int32_t max_seq_len_hint;

@@ -1,0 +1,137 @@
+"""GPU parity for the way work is spread over workgroups.  The balanced schedule lays the tiles of all
+sequences end to end and gives every workgroup an equal range, so a workgroup may hold the end of one
+sequence, several whole sequences and the start of another; sequences without tokens belong to nobody.
+These cases exercise those boundaries, the fixed-split schedule that remains for very large batches,
+and the agreement of the two.  Same oracle, same tolerances as the other parity tests."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_19427_amd as mfa
+from paper_2507_19427_amd import workloads as W
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _announce(name):
+    print(f"\n[case] {name}", flush=True)
+
+
+def _lens(seed, B, lo, hi, zeros=0):
+    g = torch.Generator().manual_seed(seed)
+    lens = torch.randint(lo, hi + 1, (B,), generator=g).tolist()
+    for i in torch.randperm(B, generator=g)[:zeros].tolist():
+        lens[i] = 0
+    return lens
+
+
+def _check(case, ctx, tol, hint=None):
+    got = U.run_gpu(ctx, case, hint=hint)
+    err = U.row_normalised_error(got, U.run_oracle(case))
+    print(f"   row-normalised max error {err:.3e}", flush=True)
+    assert err <= tol
+    for b, L in enumerate(case.seq_lens.tolist()):
+        if L == 0:
+            assert (got[b] == 0).all()
+    return got
+
+
+def test_more_sequences_than_workgroups():
+    """300 short sequences on 256 workgroups: most workgroups hold pieces of two or three sequences."""
+    _announce("B=300 short ragged, some empty")
+    lens = _lens(301, 300, 1, 200, zeros=17)
+    case = W.make_contiguous_case("many", 302, B=300, S=208, seq_lens=lens, poison=True)
+    ctx = U.get_ctx(max_batch=512, max_seq_len=4096)
+    _check(case, ctx, U.TOL_BF16)
+
+
+@pytest.mark.parametrize("lens", [
+    [0, 3000, 1, 0, 64, 5000, 129, 0, 2048],
+    [0, 0, 0, 1],
+    [4096, 0, 0, 0, 0, 0, 0, 1],
+    [63, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 65],
+])
+def test_mixed_lengths_cross_workgroup_boundaries(lens):
+    _announce(f"mixed lens={lens}")
+    S = max(lens) + 5
+    case = W.make_contiguous_case("mixed", 310 + len(lens), B=len(lens), S=S, seq_lens=lens, poison=True)
+    _check(case, U.get_ctx(), U.TOL_BF16)
+
+
+def test_fewer_tiles_than_workgroups_and_hint_far_above_lengths():
+    """The grid is sized from the hint; with short sequences most workgroups find an empty range."""
+    _announce("tiny lens under a large hint")
+    lens = [70, 1, 0, 130]
+    case = W.make_contiguous_case("tinyhint", 321, B=4, S=256, seq_lens=lens, poison=True)
+    _check(case, U.get_ctx(), U.TOL_BF16, hint=256)
+    ctx = U.get_ctx(max_batch=128, max_seq_len=32768)
+    q, lens_d = case.q.cuda(), case.seq_lens.cuda()
+    k = torch.full((4, 30000, 256), float("nan"), dtype=torch.bfloat16)
+    v = k.clone()
+    k[:, :256], v[:, :256] = case.k, case.v
+    out = mfa.mfa_decode_attn(ctx, q, k.cuda(), v.cuda(), lens_d, 30000)
+    torch.cuda.synchronize()
+    assert U.row_normalised_error(out.cpu().numpy(), U.run_oracle(case)) <= U.TOL_BF16
+
+
+def test_paged_ragged_many_sequences_bitwise_equal_to_contiguous():
+    _announce("paged B=160 ragged vs contiguous")
+    lens = _lens(331, 160, 1, 700, zeros=5)
+    case = W.make_paged_case("pagedmany", 332, lens, spare_pages=11, poison=True)
+    contig = W.paged_to_contiguous(case, S=704, poison=True)
+    ctx = U.get_ctx(max_batch=512, max_seq_len=4096)
+    got_p = _check(case, ctx, U.TOL_BF16, hint=700)
+    got_c = U.run_gpu(ctx, contig, hint=700)
+    assert np.array_equal(got_p, got_c)
+
+
+def test_fp8_more_sequences_than_workgroups():
+    _announce("fp8 B=280 short ragged")
+    lens = _lens(341, 280, 1, 300, zeros=9)
+    case = W.make_contiguous_case("fp8many", 342, B=280, S=304, seq_lens=lens, kv_dtype="fp8", poison=True)
+    ctx = U.get_ctx(max_batch=512, max_seq_len=4096)
+    _check(case, ctx, U.TOL_FP8)
+
+
+def test_fp8_mixed_lengths():
+    _announce("fp8 mixed")
+    lens = [0, 3000, 1, 0, 64, 2500, 129, 0, 2048, 65]
+    case = W.make_contiguous_case("fp8mixed", 343, B=len(lens), S=3008, seq_lens=lens, kv_dtype="fp8", poison=True)
+    _check(case, U.get_ctx(), U.TOL_FP8)
+
+
+def test_fixed_split_schedule_agrees(monkeypatch):
+    """MFA_SCHEDULE=fixed selects the schedule with equal chunks per sequence; both must match the oracle."""
+    _announce("fixed-split schedule")
+    lens = [0, 3000, 1, 64, 5000, 129, 2048]
+    case = W.make_contiguous_case("fixed", 351, B=len(lens), S=5008, seq_lens=lens, poison=True)
+    monkeypatch.setenv("MFA_SCHEDULE", "fixed")
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=16, max_seq_len=8192))
+    got_fixed = _check(case, ctx, U.TOL_BF16)
+    ctx.close()
+    monkeypatch.delenv("MFA_SCHEDULE")
+    got_bal = _check(case, U.get_ctx(), U.TOL_BF16)
+    assert U.row_normalised_error(got_fixed, got_bal.astype(np.float64)) <= U.TOL_BF16
+
+
+def test_batch_above_the_balanced_limit_uses_fixed_splits():
+    """Batches of more than 4096 sequences fall back to one workgroup per sequence."""
+    _announce("B=4100")
+    B = 4100
+    lens = _lens(361, B, 1, 64, zeros=31)
+    case = W.make_contiguous_case("huge", 362, B=B, S=64, seq_lens=lens, poison=True)
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=64))
+    _check(case, ctx, U.TOL_BF16)
+    ctx.close()
+
+
+def test_balanced_run_to_run_determinism():
+    _announce("balanced determinism")
+    lens = _lens(371, 200, 1, 900, zeros=3)
+    case = W.make_contiguous_case("det2", 372, B=200, S=904, seq_lens=lens, poison=True)
+    ctx = U.get_ctx(max_batch=512, max_seq_len=4096)
+    a = U.run_gpu(ctx, case)
+    b = U.run_gpu(ctx, case)
+    assert np.array_equal(a, b)
