@@ -134,6 +134,12 @@ MFA_API mfa_status mfa_query_proj(mfa_ctx* ctx, const void* x, const void* w_qa,
  * Scores and sums are accumulated in fp32; attention weights are rounded to
  * bf16 before they multiply V.  For a given build, device and arguments the
  * result is bitwise reproducible from call to call.
+ * Work distribution: for B <= 4096 the 64-token tiles of all sequences, laid end
+ * to end, are cut into equal ranges over at most 256 workgroups, whatever the
+ * individual lengths are (they are read on the device); larger batches, or a
+ * context created with MFA_SCHEDULE=fixed in the environment, cut every sequence
+ * into the same number of equal chunks of max_seq_len_hint instead.  Pieces of a
+ * sequence are merged in order of position by the library.
  */
 MFA_API mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
                            const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
@@ -191,9 +197,11 @@ MFA_API mfa_status mfa_debug_set_kernel_events(mfa_ctx* ctx, void* ev_before, vo
 MFA_API mfa_status mfa_debug_stream_read(mfa_ctx* ctx, const void* a, const void* b, size_t bytes_each,
                                          void* hip_stream);
 
-/* Number of context splits the next mfa_decode_attn* call with these host
- * arguments would use (each split's partial result is merged by the library).
- * Pure host function; 0 on invalid arguments. */
+/* Number of pieces into which the next mfa_decode_attn* call with these host
+ * arguments cuts a sequence of the full length max_seq_len_hint when every
+ * sequence has that length (shorter sequences get proportionally fewer; each
+ * piece's partial result is merged by the library).  Pure host function; 0 on
+ * invalid arguments. */
 MFA_API int32_t mfa_decode_num_splits(const mfa_ctx* ctx, int32_t B, int32_t max_seq_len_hint);
 
 #ifdef __cplusplus
