@@ -5,32 +5,35 @@
 //   3. bf16 MFMA GEMM writing q in bf16.
 // With at most a few hundred rows of x both products are bound by streaming the weights
 // once, so the GEMM is built like the attention kernel's value product: a workgroup owns a
-// strip of 128 output columns and all (up to 128) rows of x, streams its [K, 128] slice of
-// W through LDS with global->LDS direct loads (256 B per row, two stages of 256 rows), and
-// feeds v_mfma_f32_16x16x32_bf16 with
+// strip of 64 output columns and all (up to 128) rows of x, streams its [K, 64] slice of W
+// through LDS with global->LDS direct loads (128 B per row, two stages of 512 rows = 64 KB each,
+// one in flight while the other is multiplied), and feeds v_mfma_f32_16x16x32_bf16 with
 //   A = W^T  (16 columns x 32 k) read with the LDS transposing read,
 //   B = x^T  (32 k x 16 rows)    loaded from global memory (L2-resident) one stage ahead,
 // giving C^T[column, row]; a lane ends up with 4 consecutive columns of one row.  The eight
 // waves are 4 row groups x 2 interleaved halves of the k steps, so every x element is fetched
-// by one wave only; the two halves are added through LDS at the end.
+// by one wave only; the two halves are added through LDS at the end.  64-column strips give the
+// second product (16384 columns) 256 workgroups, one per compute unit, each with 64 KB in flight.
 #include "mfa_attn_core.hpp"
 
 namespace mfa {
 
 namespace {
 
-constexpr int kStripN = 128;                 // output columns per workgroup
-constexpr int kRowBytes = kStripN * 2;       // 256 B of W per k row
-constexpr int kStageRows = 256;              // k rows per stage
+constexpr int kStripN = 64;                  // output columns per workgroup
+constexpr int kRowBytes = kStripN * 2;       // 128 B of W per k row
+constexpr int kStageRows = 512;              // k rows per stage
 constexpr int kStageBytes = kStageRows * kRowBytes;   // 64 KB
 constexpr int kGemmLdsBytes = 2 * kStageBytes;
 constexpr int kGemmThreads = 512;
 constexpr int kStepsPerStage = kStageRows / 32;
+constexpr int kColBlocks = kStripN / 16;
 
-// Swizzle key of a W row in LDS: its 32-byte chunk c is stored at position c ^ key.  The 16 rows
-// touched by one transposing read (rows 8g + 4t + i, g = 0..3, i = 0..3) get keys 2g + i/2, so the
-// 16 x 32 B of the read spread over all eight 32-byte positions of the 256-byte row.
-__device__ __forceinline__ int w_key(int row) { return (((row >> 3) & 3) << 1) | ((row >> 1) & 1); }
+// Swizzle key of a W row in LDS: its 32-byte chunk c is stored at position c ^ key.  A transposing
+// read touches rows 8g + 4t + i (g = 0..3, i = 0..3) at one chunk each.  Rows are 128 bytes, so rows
+// of equal parity share their banks; with key = 2*(g & 1) + i/2 the four rows of equal parity read
+// by each half of the wave (g = 0, 1 or g = 2, 3) take the four chunk positions once each.
+__device__ __forceinline__ int w_key(int row) { return (((row >> 3) & 1) << 1) | ((row >> 1) & 1); }
 
 // OUT_BF16 = false: fp32 partial sums to out[(kz*rows_pad + m)*N + n] for every row of the tile.
 // OUT_BF16 = true : bf16 result to out[m*N + n] for m < M (requires gridDim.z == 1).
@@ -61,17 +64,17 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
     const int k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
     const int n_stages = (k_end - k_begin + kStageRows - 1) / kStageRows;
 
-    // Direct load of one stage of W: 64 loads of 4 rows; wave w issues loads 8w .. 8w+7.
+    // Direct load of one stage of W: 64 loads of 8 rows; wave w issues loads 8w .. 8w+7.
     auto issue_stage = [&](int stage, int slot) {
         const int k0 = k_begin + stage * kStageRows;
         const int rows_valid = (k_end - k0 < kStageRows) ? k_end - k0 : kStageRows;   // multiple of 32
-        const int p16 = lane & 15;
+        const int p8 = lane & 7;                                       // 16-byte position in the 128-byte row
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int first_row = 4 * (8 * wave + i);                  // wave-uniform
+            const int first_row = 8 * (8 * wave + i);                  // wave-uniform
             if (first_row < rows_valid) {
-                const int row = first_row + (lane >> 4);
-                const int c16 = ((((p16 >> 1) ^ w_key(row)) << 1) | (p16 & 1));
+                const int row = first_row + (lane >> 3);
+                const int c16 = ((((p8 >> 1) ^ w_key(row)) << 1) | (p8 & 1));
                 const unsigned char* src = (const unsigned char*)W + ((size_t)(k0 + row) * N + n0) * 2 + c16 * 16;
                 load_to_lds_16B(src, lds_addr0 + slot * kStageBytes + first_row * kRowBytes);
             }
@@ -80,6 +83,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
 
     // x fragments of this wave's k steps of one stage: lane (row n of a 16-row block, k group g)
     // holds x[row][k0 + 32*(2j + kh) + 8g .. +7].  Every x element is loaded by exactly one wave.
+    // Two sets: the next stage's fragments are requested right after its W, a whole stage ahead.
     constexpr int kMySteps = kStepsPerStage / 2;
     bf16x8 xf[2][2][kMySteps];                // [buffer][row block][own k step]
     int xrow[2];
@@ -103,85 +107,113 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
         }
     };
 
-    f32x4 acc[2][8];
+    f32x4 acc[2][kColBlocks];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < kColBlocks; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     const int a_lane_off = (8 * g + (n >> 2)) * kRowBytes + ((n & 3) << 3);   // row 8g + i, 8 bytes per lane
-    const int a_key = (g << 1) | ((n >> 3) & 1);                             // w_key of rows 8g + 4t + i: 2g + i/2
+    const int a_key = ((g & 1) << 1) | ((n >> 3) & 1);                        // w_key of rows 8g + 4t + i
 
-    auto compute_step = [&](int base, int ks, const bf16x8& x0, const bf16x8& x1) {
+    // A operands of one k step: for each 16-column block the two transposing reads that make W^T.
+    struct AFrag { union { bf16x8 v; s16x4 h[2]; } nb[kColBlocks]; };
+    auto read_a = [&](AFrag& f, int base, int ks) {
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) {
-            union { bf16x8 v; s16x4 h[2]; } wf;
+        for (int nb = 0; nb < kColBlocks; ++nb)
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int off = base + (32 * ks + 4 * t) * kRowBytes + a_lane_off + ((nb ^ a_key) << 5);
-                wf.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
+                f.nb[nb].h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
             }
-            acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, x0, acc[0][nb], 0, 0, 0);
-            acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, x1, acc[1][nb], 0, 0, 0);
+    };
+    auto multiply = [&](const AFrag& f, const bf16x8& x0, const bf16x8& x1) {
+#pragma unroll
+        for (int nb = 0; nb < kColBlocks; ++nb) {
+            acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.nb[nb].v, x0, acc[0][nb], 0, 0, 0);
+            acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.nb[nb].v, x1, acc[1][nb], 0, 0, 0);
         }
     };
+    // The A operands of the next own step are read from LDS while the current one is multiplied, so
+    // that the LDS latency hides behind eight MFMAs instead of stalling each pair.
     auto compute_stage = [&](int stage, int slot, int buf) {
         const int k0 = k_begin + stage * kStageRows;
         const int steps = ((k_end - k0 < kStageRows) ? k_end - k0 : kStageRows) / 32;
         const int base = slot * kStageBytes;
-        if (steps == kStepsPerStage) {                 // full stage: straight-line code the scheduler can interleave
+        AFrag fa, fb;
+        if (steps == kStepsPerStage) {                 // full stage: straight-line code
+            // (the scheduling fences keep the compiler from sinking the reads back to their uses)
+            read_a(fa, base, kh);
 #pragma unroll
-            for (int j = 0; j < kMySteps; ++j) compute_step(base, 2 * j + kh, xf[buf][0][j], xf[buf][1][j]);
+            for (int j = 0; j < kMySteps; j += 2) {
+                read_a(fb, base, 2 * (j + 1) + kh);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(fa, xf[buf][0][j], xf[buf][1][j]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (j + 2 < kMySteps) read_a(fa, base, 2 * (j + 2) + kh);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(fb, xf[buf][0][j + 1], xf[buf][1][j + 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         } else {
 #pragma unroll
             for (int j = 0; j < kMySteps; ++j)
-                if (2 * j + kh < steps) compute_step(base, 2 * j + kh, xf[buf][0][j], xf[buf][1][j]);
+                if (2 * j + kh < steps) {
+                    read_a(fa, base, 2 * j + kh);
+                    multiply(fa, xf[buf][0][j], xf[buf][1][j]);
+                }
         }
     };
 
-    issue_stage(0, 0);
-    load_x_stage(0, 0);
+    // While a stage is multiplied the next one (W by direct loads, x into the other register set) is
+    // in flight; everything requested is awaited at the barrier that opens a stage.
+    // Workgroups walk the stages of their k range starting at different points (strip index modulo
+    // the stage count) and wrapping round: at any moment the strips that share an L2 then ask it for
+    // different parts of x instead of all for the same lines.
+    const int phase = (int)((blockIdx.x >> 3) % (unsigned)n_stages);   // workgroups 8 apart share an XCD's L2
+    auto stage_of = [&](int it) { const int s = it + phase; return s < n_stages ? s : s - n_stages; };
+    issue_stage(stage_of(0), 0);
+    load_x_stage(stage_of(0), 0);
     for (int st = 0; st < n_stages; st += 2) {
-        // even stage: slot 0, x buffer 0
+        // even step: slot 0, x buffer 0
         wait_vmem_all();
         __syncthreads();
-        if (st + 1 < n_stages) { issue_stage(st + 1, 1); load_x_stage(st + 1, 1); }
-        compute_stage(st, 0, 0);
+        if (st + 1 < n_stages) { issue_stage(stage_of(st + 1), 1); load_x_stage(stage_of(st + 1), 1); }
+        compute_stage(stage_of(st), 0, 0);
         if (st + 1 >= n_stages) break;
-        // odd stage: slot 1, x buffer 1
+        // odd step: slot 1, x buffer 1
         wait_vmem_all();
         __syncthreads();
-        if (st + 2 < n_stages) { issue_stage(st + 2, 0); load_x_stage(st + 2, 0); }
-        compute_stage(st + 1, 1, 1);
+        if (st + 2 < n_stages) { issue_stage(stage_of(st + 2), 0); load_x_stage(stage_of(st + 2), 0); }
+        compute_stage(stage_of(st + 1), 1, 1);
     }
 
     // The two waves that share 32 rows (kh = 0, 1) hold sums over disjoint k steps: exchange halves
     // through LDS (the stage buffers are dead, no direct load is in flight); kh 0 finishes column
-    // blocks 0..3, kh 1 blocks 4..7.  Fixed order (own + other with kh 0's share first) keeps the
-    // result reproducible.
+    // blocks 0..1, kh 1 blocks 2..3.  Fixed order ((kh 0 part) + (kh 1 part)) keeps the result
+    // reproducible.
     __syncthreads();
     {
-        const int mine = (mp * 2 + kh) * 8;           // 8 slots of 1 KB: [row block][4 column blocks]
-        const int theirs = (mp * 2 + (kh ^ 1)) * 8;
-        const int send = kh == 0 ? 4 : 0;
+        constexpr int kHalf = kColBlocks / 2;
+        const int mine = (mp * 2 + kh) * 2 * kHalf;   // slots of 1 KB: [row block][kHalf column blocks]
+        const int theirs = (mp * 2 + (kh ^ 1)) * 2 * kHalf;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const f32x4 v = kh == 0 ? acc[mb][4 + j] : acc[mb][j];
-                *LDS_AT(f32x4, lds_base, (mine + mb * 4 + j) * 1024 + lane * 16) = v;
+            for (int j = 0; j < kHalf; ++j) {
+                const f32x4 v = kh == 0 ? acc[mb][kHalf + j] : acc[mb][j];
+                *LDS_AT(f32x4, lds_base, (mine + mb * kHalf + j) * 1024 + lane * 16) = v;
             }
-        (void)send;
         __syncthreads();
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             const int m = m0 + 32 * mp + 16 * mb + n;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const f32x4 other = *LDS_AT(f32x4, lds_base, (theirs + mb * 4 + j) * 1024 + lane * 16);
-                const f32x4 own = kh == 0 ? acc[mb][j] : acc[mb][4 + j];
+            for (int j = 0; j < kHalf; ++j) {
+                const f32x4 other = *LDS_AT(f32x4, lds_base, (theirs + mb * kHalf + j) * 1024 + lane * 16);
+                const f32x4 own = kh == 0 ? acc[mb][j] : acc[mb][kHalf + j];
                 const f32x4 r = kh == 0 ? own + other : other + own;     // always (kh 0 part) + (kh 1 part)
-                const int col = n0 + 16 * (4 * kh + j) + 4 * g;
+                const int col = n0 + 16 * (kHalf * kh + j) + 4 * g;
                 if (OUT_BF16) {
                     if (m < M) {
                         union { __bf16 h[4]; uint2 u; } o;
