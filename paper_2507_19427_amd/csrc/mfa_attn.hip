@@ -30,18 +30,16 @@ namespace mfa {
 constexpr int kSlotBytes = 2 * kUnitBytes;            // one 64-token tile: two unit images
 constexpr int kAttnLdsBytes = 2 * kSlotBytes;         // bf16 kernel: 128 KB
 
-// fp8 kernel: two bf16 tile images, then per image 64 key scales and 64 value scales (fp32)
-constexpr int kFp8ScaleBase = 2 * kSlotBytes;
-constexpr int kFp8LdsBytes = 2 * kSlotBytes + 2 * 512;
-static_assert(kFp8LdsBytes <= kSchedLdsOffset && kAttnLdsBytes <= kSchedLdsOffset && kAttnLdsTotal <= 160 * 1024,
-              "the schedule's prefix sums live behind the tile memory of both kernels");
 
 // Page id of the tile that starts at token tile_t0 (paged cache only).  Looked up one tile ahead
 // of its use so that the table read is never on the critical path of issuing a tile's loads.
 template <bool PAGED>
 __device__ __forceinline__ int lookup_page(const AttnArgs& a, int b, int tile_t0)
 {
-    return PAGED ? a.block_table[(size_t)b * a.max_blocks_per_seq + tile_t0 / kPage] : 0;
+    // read through the constant address space: the table is not written while the kernel runs, and a
+    // uniform index then makes this a scalar load, which the vector-memory waits do not have to cover
+    typedef const __attribute__((address_space(4))) int32_t* const_table_t;
+    return PAGED ? ((const_table_t)a.block_table)[(size_t)b * a.max_blocks_per_seq + tile_t0 / kPage] : 0;
 }
 
 template <bool PAGED>
@@ -71,8 +69,8 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
         if (!first_segment) __syncthreads();          // the previous segment's exchange area is the tile memory
         first_segment = false;
 
-        bf16x8 qf[8];
-        load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
+        QFrags<false> q;
+        load_q_fragments(q.f, a.q, r.b, 16 * wq + n, g);
 
         // Wave w brings rows [8w, 8w+8) of the tile's K and V: all in unit w/4.  Rows at or past t1
         // re-read the last valid token, so nothing outside the sequence is touched and every LDS row
@@ -112,27 +110,42 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
                 issue_tile(it + 1, slot ^ 1, page_next);
                 if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
             }
-            process_unit<false>(st, qf, lds_base, slot * kSlotBytes + grp * kUnitBytes,
-                                r.t0 + it * kTile + grp * kUnitTokens, r.t1, a.scale_log2e, n, g, 0, 0);
+            const int unit = slot * kSlotBytes + grp * kUnitBytes;
+            process_unit<false>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + grp * kUnitTokens,
+                                r.t1, a.scale_log2e, n, g, 0, 0);
         }
         finish_segment(st, lds_base, a, r, wq, grp, lane);
     }
 }
 
-// One tile of fp8 codes held in registers on its way from HBM to the bf16 LDS image: the
-// workgroup's 512 threads each own four 16-byte pieces (two of K, two of V) and, for the first
-// 128 threads, one per-token scale.
-struct Fp8TileRegs {
-    u32x4 piece[4];
-    float scale;
-};
-constexpr int kFp8LoadsPerTile = 5;
+// ---- fp8 cache.
+// Keys stay e4m3 codes all the way: each tile's 16 KB go by direct loads into a ring of three LDS
+// slots and are multiplied on the fp8 MFMA against the two-term query.  Values are multiplied by
+// bf16 weights, so their codes are converted once per tile: every thread carries two 16-byte pieces
+// of V and one per-token scale in registers from HBM, converts (exactly: every e4m3 value is a bf16
+// value) and writes the swizzled bf16 rows into one of two value images.
+//
+// LDS: value image P (P = tile & 1) at P*32 KB, its unit g at + g*16 KB; key slot k (tile % 3) at
+// 64 KB + k*16 KB; scale set P at 112 KB + P*512 B (64 key scales, then 64 value scales).
+constexpr int kFp8VImageBytes = 2 * 16384;
+constexpr int kFp8KBase = 2 * kFp8VImageBytes;
+constexpr int kFp8KSlotBytes = kTile * 256;
+constexpr int kFp8KSlots = 3;
+constexpr int kFp8ScaleBase = kFp8KBase + kFp8KSlots * kFp8KSlotBytes;
+constexpr int kFp8LdsBytes = kFp8ScaleBase + 2 * 512;
+static_assert(kFp8LdsBytes <= kSchedLdsOffset && kAttnLdsBytes <= kSchedLdsOffset && kAttnLdsTotal <= 160 * 1024,
+              "the schedule's prefix sums live behind the tile memory of both kernels");
 
-// The loads of the register pipeline are issued as inline assembly and awaited with an explicit
-// vmcnt that leaves exactly the newer tile's loads in flight; left to the compiler, the wait for the
-// older tile is widened to vmcnt(0) at the loop's control-flow joins, which drains the pipeline every
-// tile.  wait_tile() passes the registers through the waiting statement, so no use of them can be
-// scheduled before it.
+struct Fp8TileRegs {
+    u32x4 piece[2];       // V rows prow and prow + 32, 16-byte chunk pchunk
+    float scale;          // threads 0..63: key scale of token tid; 64..127: value scale of token tid - 64
+};
+// Every step of the pipeline issues, per wave and in this order, the three register loads of a
+// tile and the two direct loads of a key tile.  They are inline assembly, awaited with an explicit
+// vmcnt that leaves exactly the youngest step's five in flight: left to the compiler, the wait would
+// be widened to vmcnt(0) at the loop's control-flow joins and drain the pipeline every tile.  The
+// registers pass through the waiting statement, so no use of them can be scheduled before it.
+constexpr int kFp8OpsPerStep = 5;
 __device__ __forceinline__ void load_regs_16B(u32x4& dst, const void* p)
 {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
@@ -141,20 +154,18 @@ __device__ __forceinline__ void load_regs_4B(float& dst, const void* p)
 {
     asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
 }
-__device__ __forceinline__ void wait_tile_older_of_two(Fp8TileRegs& t)
+__device__ __forceinline__ void wait_all_but_youngest_step(Fp8TileRegs& t)
 {
-    static_assert(kFp8LoadsPerTile == 5, "the wait below leaves 5 loads in flight");
-    asm volatile("s_waitcnt vmcnt(5)"
-                 : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.piece[2]), "+v"(t.piece[3]), "+v"(t.scale) :: "memory");
+    static_assert(kFp8OpsPerStep == 5, "the wait below leaves 5 operations in flight");
+    asm volatile("s_waitcnt vmcnt(5)" : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.scale) :: "memory");
 }
-
 // Wait for every load in flight while both register sets are still owned by the pipeline: no
 // register of theirs may be handed to other code before its load has landed.
 __device__ __forceinline__ void drain_tiles(Fp8TileRegs& t, Fp8TileRegs& u)
 {
     asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.piece[2]), "+v"(t.piece[3]), "+v"(t.scale),
-                   "+v"(u.piece[0]), "+v"(u.piece[1]), "+v"(u.piece[2]), "+v"(u.piece[3]), "+v"(u.scale) :: "memory");
+                 : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.scale), "+v"(u.piece[0]), "+v"(u.piece[1]), "+v"(u.scale)
+                 :: "memory");
 }
 
 template <bool PAGED>
@@ -162,6 +173,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const lds_ptr_t lds_base = (lds_ptr_t)smem;
+    const uint32_t lds_addr0 = (uint32_t)(uintptr_t)lds_base;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -177,39 +189,48 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
         if (!first_segment) __syncthreads();          // the previous segment's exchange area is the tile memory
         first_segment = false;
 
-        // Piece i of this thread: tensor (i >> 1 ? V : K), row (threadIdx.x >> 4) + 32*(i & 1), 16-byte
-        // chunk threadIdx.x & 15, so that consecutive threads read consecutive 16 bytes.  Rows at or
-        // past t1 re-read the last valid token.
+        // Tiles past the end of the segment repeat its last tile (never consumed), so that every step
+        // issues the same number of loads.  Rows at or past t1 re-read the last valid token.
         const int prow = threadIdx.x >> 4;
         const int pchunk = threadIdx.x & 15;
+        auto tile_origin = [&](int tile, int& tile_t0, int64_t& row0, int& last) {
+            if (tile >= r.n_tiles) tile = r.n_tiles - 1;
+            tile = __builtin_amdgcn_readfirstlane(tile);                   // keeps the page lookup a scalar load
+            tile_t0 = r.t0 + tile * kTile;
+            row0 = tile_row0<PAGED>(a, r.b, tile_t0, lookup_page<PAGED>(a, r.b, tile_t0));
+            last = r.t1 - 1 - tile_t0;                                    // last valid row of this tile (>= 0)
+        };
         auto load_tile = [&](Fp8TileRegs& t, int tile) {
-            if (tile >= r.n_tiles) tile = r.n_tiles - 1;   // past the end: re-read the last tile (never consumed)
-            const int tile_t0 = r.t0 + tile * kTile;
-            const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, lookup_page<PAGED>(a, r.b, tile_t0));
-            const int last = r.t1 - 1 - tile_t0;                          // last valid row of this tile (>= 0)
+            int tile_t0, last; int64_t row0;
+            tile_origin(tile, tile_t0, row0, last);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = prow + 32 * (i & 1);
+            for (int i = 0; i < 2; ++i) {
+                const int row = prow + 32 * i;
                 const int in_tile = row > last ? last : row;
-                const unsigned char* base = (const unsigned char*)((i >> 1) ? a.v : a.k);
-                load_regs_16B(t.piece[i], base + (size_t)(row0 + in_tile) * 256 + pchunk * 16);
+                load_regs_16B(t.piece[i], (const unsigned char*)a.v + (size_t)(row0 + in_tile) * 256 + pchunk * 16);
             }
-            {
-                // every thread loads a scale (threads 128.. repeat those of 0..127) so that the loads of a
-                // tile form one straight-line group: the wait for an older tile can then leave the newer
-                // tile's loads in flight
-                const int tok = threadIdx.x & 63;
-                const int in_tile = tok > last ? last : tok;
-                load_regs_4B(t.scale, ((threadIdx.x & 64) ? a.v_scale : a.k_scale) + (row0 + in_tile));
+            const int tok = threadIdx.x & 63;                              // threads 128.. repeat those of 0..127
+            const int in_tile = tok > last ? last : tok;
+            load_regs_4B(t.scale, ((threadIdx.x & 64) ? a.v_scale : a.k_scale) + (row0 + in_tile));
+        };
+        // Keys of a tile: 16 direct loads of 4 rows; wave w issues loads 2w and 2w + 1.
+        auto issue_keys = [&](int tile, int kslot) {
+            int tile_t0, last; int64_t row0;
+            tile_origin(tile, tile_t0, row0, last);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int first_row = 4 * (2 * wave + i);                     // wave-uniform
+                const int row = first_row + (lane >> 4);
+                const int in_tile = row > last ? last : row;
+                const int c16 = (lane & 15) ^ (row & 15);
+                load_to_lds_16B((const unsigned char*)a.k + (size_t)(row0 + in_tile) * 256 + c16 * 16,
+                                lds_addr0 + kFp8KBase + kslot * kFp8KSlotBytes + first_row * 256);
             }
         };
-
-        // Convert a tile's codes to bf16 (exact: every e4m3 value is a bf16 value) and write them into
-        // image `slot` in the swizzled unit layout; the scales go beside it.
-        auto store_tile = [&](const Fp8TileRegs& t, int slot) {
-            const int image = slot * kSlotBytes;
+        // Convert a tile's value codes to bf16 and write them into image `image`; the scales go beside it.
+        auto store_tile = [&](const Fp8TileRegs& t, int image) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 2; ++i) {
                 bf16x8 half[2];
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
@@ -221,48 +242,46 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
                     half[w >> 1][4 * (w & 1) + 3] = (__bf16)f23[1];
                 }
                 const int key = prow & 15;                                 // row within its unit = prow (0..31)
-                const int unit = image + (i & 1) * kUnitBytes + prow * 512;
-                if (i >> 1) {
-                    const int off = unit + kUnitVOffset + ((pchunk ^ key) << 5);
-                    *LDS_AT(bf16x8, lds_base, off) = half[0];
-                    *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
-                } else {
-                    *LDS_AT(bf16x8, lds_base, unit + (((2 * pchunk) ^ key) << 4)) = half[0];
-                    *LDS_AT(bf16x8, lds_base, unit + (((2 * pchunk + 1) ^ key) << 4)) = half[1];
-                }
+                const int off = image * kFp8VImageBytes + i * 16384 + prow * 512 + ((pchunk ^ key) << 5);
+                *LDS_AT(bf16x8, lds_base, off) = half[0];
+                *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
             }
-            if (threadIdx.x < 128) *LDS_AT(float, lds_base, kFp8ScaleBase + slot * 512 + threadIdx.x * 4) = t.scale;
+            if (threadIdx.x < 128) *LDS_AT(float, lds_base, kFp8ScaleBase + image * 512 + threadIdx.x * 4) = t.scale;
         };
 
         WaveState st;
         init_state(st);
 
-        // Pipeline: tile t+2 (and t+3) travel from HBM to registers while tile t+1 is converted into the
-        // other LDS image and tile t is consumed from its image; one barrier per tile.
+        // Step t consumes tile t (value image t & 1, key slot t % 3) while it converts the values of
+        // tile t+1 into the other image and has the registers of tiles t+2, t+3 and the keys of tiles
+        // t+1, t+2 in flight.  Prologue: what steps -2 and -1 would have issued.
         Fp8TileRegs regs[2];
-        // The loads of every step are issued unconditionally (clamped to the last tile) so that exactly
-        // two tiles' loads are outstanding whenever one is awaited.
         load_tile(regs[0], 0);
         load_tile(regs[1], 1);
-        // The query fragments are loaded by ordinary loads and pinned here: the compiler completes them
-        // (and with them the two tiles above) before the loop, instead of waiting for them, and so for
-        // every load in flight, inside it.
-        bf16x8 qf[8];
-        load_q_fragments(qf, a.q, r.b, 16 * wq + n, g);
-        asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7]));
-        wait_tile_older_of_two(regs[0]);
+        issue_keys(0, 0);
+        // The query fragments are loaded by ordinary loads: the compiler completes them, and with them
+        // everything above, right here instead of inside the loop.
+        QFrags<true> q;
+        load_split_q_fp8(q, a.q, r.b, 16 * wq + n, g);
+        asm volatile("" : "+v"(q.hi[0]), "+v"(q.hi[1]), "+v"(q.lo[0]), "+v"(q.lo[1]));
+        drain_tiles(regs[0], regs[1]);
         store_tile(regs[0], 0);
         load_tile(regs[0], 2);
+        issue_keys(1, 1);
 
+        int kslot = 0;                                                     // t % 3
         auto step = [&](auto parity_c, int t) {
             constexpr int P = decltype(parity_c)::value;                    // t & 1
-            __syncthreads();              // image P holds tile t; everyone is done with image P^1 (tile t-1)
-            wait_tile_older_of_two(regs[P ^ 1]);
-            store_tile(regs[P ^ 1], P ^ 1);                                 // tile t+1 (a repeat of the last tile at the end)
+            wait_all_but_youngest_step(regs[P ^ 1]);       // registers of tile t+1 and keys of tile t have landed
+            __syncthreads();                               // ... for every wave; everyone is done with tile t-1
+            store_tile(regs[P ^ 1], P ^ 1);                                 // values of tile t+1
             load_tile(regs[P ^ 1], t + 3);
+            issue_keys(t + 2, kslot == 0 ? 2 : kslot - 1);                  // (t + 2) % 3, the slot tile t-1 has left
             const int scales = kFp8ScaleBase + P * 512 + grp * kUnitTokens * 4;
-            process_unit<true>(st, qf, lds_base, P * kSlotBytes + grp * kUnitBytes, r.t0 + t * kTile + grp * kUnitTokens,
-                               r.t1, a.scale_log2e, n, g, scales, scales + 256);
+            process_unit<true>(st, q, lds_base, kFp8KBase + kslot * kFp8KSlotBytes + grp * kUnitTokens * 256,
+                               P * kFp8VImageBytes + grp * 16384, r.t0 + t * kTile + grp * kUnitTokens, r.t1,
+                               a.scale_log2e, n, g, scales, scales + 256);
+            kslot = kslot == 2 ? 0 : kslot + 1;
         };
         for (int t = 0; t < r.n_tiles; t += 2) {
             step(std::integral_constant<int, 0>{}, t);

@@ -100,31 +100,109 @@ __device__ __forceinline__ void load_q_fragments(bf16x8 (&qf)[8], const void* q,
     for (int ks = 0; ks < 8; ++ks) qf[ks] = qp[ks * 4];
 }
 
-// One 32-token unit: scores, online softmax, weighted sum.
-//   unit_base  LDS byte offset of the unit image
-//   unit_t0    index (within the sequence) of the unit's first token; tokens >= t1 are masked
-//   FP8        the image holds unscaled codes converted to bf16; kscale/vscale point (LDS byte
-//              offsets) at the fp32 per-token scales of the unit's 32 tokens
-template <bool FP8>
-__device__ __forceinline__ void process_unit(WaveState& st, const bf16x8 (&qf)[8], lds_ptr_t lds_base, int unit_base,
-                                             int unit_t0, int t1, float scale_log2e, int n, int g, int kscale_off,
-                                             int vscale_off)
+// Query operands of one wave (its 16 heads).
+//   bf16 cache: the bf16 fragments as loaded; a lane holds head n, d = 32*ks + 8*g + j.
+//   fp8 cache:  the scores are taken on the fp8 MFMA (v_mfma_f32_16x16x128_f8f6f4, twice the bf16
+//               rate) straight from the cache's codes, so the query is split into two e4m3 terms,
+//               q * 2^e = hi + lo with e chosen per head so that the largest |q| of the head lands in
+//               [128, 256): hi is the nearest e4m3 value and lo the remainder, which e4m3 holds
+//               exactly (the 8 significant bits of bf16 are 4 + 4) down to 2^-9, i.e. to 2^-17 of the
+//               head's largest element.  A lane holds head n, d = 128*c + 32*g + j (j = 0..31, one
+//               byte each, in register order); inv_scale = 2^-e.
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+template <bool FP8> struct QFrags;
+template <> struct QFrags<false> { bf16x8 f[8]; };
+template <> struct QFrags<true> { i32x8 hi[2]; i32x8 lo[2]; float inv_scale; };
+
+__device__ __forceinline__ void load_split_q_fp8(QFrags<true>& q, const void* qptr, int b, int head, int g)
 {
-    const int kbase = unit_base;
-    const int vbase = unit_base + kUnitVOffset;
-    const int k_lane_off = n * 512;                     // K: row n of a 16-token block, swizzle key n
+    const bf16x8* qp = (const bf16x8*)((const uint16_t*)qptr + ((size_t)b * kHeads + head) * kHeadDim + 32 * g);
+    bf16x8 qf[2][4];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qf[c][i] = qp[c * 16 + i];
+    float amax = 0.f;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf((float)qf[c][i][j]));
+    amax = head_max(amax);
+    int e = (int)((__float_as_uint(amax) >> 23) & 0xFFu);          // biased exponent of the largest element
+    e = e < 24 ? 24 : e;                                           // (all-zero or vanishing heads: any scale will do)
+    const float scale = __uint_as_float((uint32_t)(261 - e) << 23);   // amax * scale in [128, 256)
+    q.inv_scale = __uint_as_float((uint32_t)(e - 7) << 23);
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int w = 0; w < 2; ++w) {
+                float x[4], r[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) x[j] = (float)qf[c][i][4 * w + j] * scale;
+                int h = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], 0, false);
+                h = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], h, true);
+                const auto h01 = __builtin_amdgcn_cvt_pk_f32_fp8(h, false);
+                const auto h23 = __builtin_amdgcn_cvt_pk_f32_fp8(h, true);
+                r[0] = x[0] - h01[0]; r[1] = x[1] - h01[1]; r[2] = x[2] - h23[0]; r[3] = x[3] - h23[1];
+                int l = __builtin_amdgcn_cvt_pk_fp8_f32(r[0], r[1], 0, false);
+                l = __builtin_amdgcn_cvt_pk_fp8_f32(r[2], r[3], l, true);
+                q.hi[c][2 * i + w] = h;
+                q.lo[c][2 * i + w] = l;
+            }
+}
+
+// One 32-token unit: scores, online softmax, weighted sum.
+//   kbase      LDS byte offset of the unit's keys:
+//                bf16: 32 rows of 512 B, 16-byte chunk c of row r stored at c ^ (r & 15)
+//                fp8:  32 rows of 256 B of e4m3 codes, 16-byte chunk c of row r at c ^ (r & 15)
+//   vbase      LDS byte offset of the unit's values: 32 rows of 512 B of bf16 (fp8: the codes
+//              converted, unscaled), 32-byte chunk c of row r stored at c ^ (r & 15)
+//   unit_t0    index (within the sequence) of the unit's first token; tokens >= t1 are masked
+//   FP8        kscale/vscale point (LDS byte offsets) at the fp32 per-token scales of the unit's 32 tokens
+template <bool FP8>
+__device__ __forceinline__ void process_unit(WaveState& st, const QFrags<FP8>& q, lds_ptr_t lds_base, int kbase,
+                                             int vbase, int unit_t0, int t1, float scale_log2e, int n, int g,
+                                             int kscale_off, int vscale_off)
+{
     const int v_row = 4 * g + (n >> 2);                 // V: row within a 16-token block = swizzle key
     const int v_lane_off = v_row * 512 + ((n & 3) << 3);
 
     // ---- scores for 2 blocks of 16 tokens
     f32x4 s[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
+    if constexpr (FP8) {
+        // e4m3 x e4m3 with unit block scales (E8M0 exponent 127)
+        constexpr int kOne = 0x7F7F7F7F;
+        f32x4 slo[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+        for (int c = 0; c < 2; ++c) {
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            const int off = kbase + tb * 8192 + k_lane_off + (((4 * ks + g) ^ n) << 4);
-            const bf16x8 kf = *LDS_AT(bf16x8, lds_base, off);
-            s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s[tb], 0, 0, 0);
+            for (int tb = 0; tb < 2; ++tb) {
+                const int row = kbase + tb * 4096 + n * 256;
+                const int m = 8 * c + 2 * g;                       // first of this lane's two 16-byte chunks
+                union { i32x8 v; u32x4 h[2]; } kf;
+                kf.h[0] = *LDS_AT(u32x4, lds_base, row + ((m ^ n) << 4));
+                kf.h[1] = *LDS_AT(u32x4, lds_base, row + (((m + 1) ^ n) << 4));
+                s[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf.v, q.hi[c], s[tb], 0, 0, 0, kOne, 0, kOne);
+                slo[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf.v, q.lo[c], slo[tb], 0, 0, 0, kOne, 0, kOne);
+            }
+        }
+        s[0] += slo[0];                                  // four independent chains, joined here
+        s[1] += slo[1];
+        scale_log2e *= q.inv_scale;
+    } else {
+        const int k_lane_off = n * 512;                 // K: row n of a 16-token block, swizzle key n
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const int off = kbase + tb * 8192 + k_lane_off + (((4 * ks + g) ^ n) << 4);
+                const bf16x8 kf = *LDS_AT(bf16x8, lds_base, off);
+                s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, q.f[ks], s[tb], 0, 0, 0);
+            }
         }
     }
     f32x4 vsc[2];
