@@ -332,3 +332,82 @@ ORACLE_API int mfa_oracle_query_proj(const uint16_t *x, const uint16_t *w_qa, co
     free(wa); free(wb);
     return 0;
 }
+
+/* ------------------------------------------------------------------ */
+/* The linear maps around the attention core and the writing of a new   */
+/* token into the cache (Section 6 counts them in the attention layer:  */
+/* key and value projections 7168 -> 256 each, output projection        */
+/* 64*256 -> 7168; the cache holds 8-bit keys and values).              */
+/* ------------------------------------------------------------------ */
+
+/* y = a . w in double.  a: [B, K], bf16 bit patterns (a_is_f32 = 0) or fp32 values (a_is_f32 = 1);
+ * w: bf16 [K, N] (in x out); y: double [B, N]. */
+ORACLE_API int mfa_oracle_linear(const void *a, int a_is_f32, const uint16_t *w, int B, int K, int N, double *y)
+{
+    int nthreads = mfa_oracle_get_threads();
+    (void)nthreads;
+    double *wd = (double *)malloc(sizeof(double) * (size_t)K * N);
+    if (!wd) return 2;
+    for (int64_t i = 0; i < (int64_t)K * N; ++i) wd[i] = decode_bf16(w[i]);
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int b = 0; b < B; ++b) {
+        double *row = y + (int64_t)b * N;
+        for (int n = 0; n < N; ++n) row[n] = 0.0;
+        for (int k = 0; k < K; ++k) {
+            double ak = a_is_f32 ? (double)((const float *)a)[(int64_t)b * K + k]
+                                 : decode_bf16(((const uint16_t *)a)[(int64_t)b * K + k]);
+            const double *wrow = wd + (int64_t)k * N;
+            for (int n = 0; n < N; ++n) row[n] += ak * wrow[n];
+        }
+    }
+    free(wd);
+    return 0;
+}
+
+/* Nearest e4m3fn code of a finite float with |x| <= 448, ties to the even code.
+ * Normal numbers 2^e (1 + m/8), e = -6..8; below 2^-6 the spacing is 2^-9. */
+static uint8_t encode_e4m3fn_rne(float x)
+{
+    uint8_t sign = (uint8_t)(signbit(x) ? 0x80 : 0x00);
+    double a = fabs((double)x);
+    if (a >= 448.0) return (uint8_t)(sign | 0x7E);
+    if (a < 0.015625) {                              /* subnormal range: code = a / 2^-9, 8 rolls over into 2^-6 */
+        double q = nearbyint(a * 512.0);             /* default rounding mode: to nearest, ties to even */
+        return (uint8_t)(sign | (uint8_t)q);
+    }
+    int e;
+    double f = frexp(a, &e);                         /* a = f 2^e, f in [0.5, 1) */
+    f *= 2.0; e -= 1;                                /* a = f 2^e, f in [1, 2) */
+    double m = nearbyint((f - 1.0) * 8.0);           /* 0..8 */
+    if (m == 8.0) { m = 0.0; e += 1; }
+    if (e > 8 || (e == 8 && m > 6.0)) return (uint8_t)(sign | 0x7E);
+    return (uint8_t)(sign | (uint8_t)((e + 7) << 3) | (uint8_t)m);
+}
+
+/* Per-token quantisation of cache rows, defined in single precision because floating point
+ * decides integer codes here: scale = max(max_d |x_d|, 1e-12) / 448, code_d = e4m3fn(x_d / scale)
+ * with the quotient clamped to [-448, 448].  x: fp32 [rows, D]. */
+ORACLE_API int mfa_oracle_quantize_rows_e4m3(const float *x, int rows, int D, uint8_t *codes, float *scales)
+{
+    for (int r = 0; r < rows; ++r) {
+        const float *row = x + (int64_t)r * D;
+        float amax = 0.0f;
+        for (int d = 0; d < D; ++d) amax = fmaxf(amax, fabsf(row[d]));
+        volatile float scale = fmaxf(amax, 1e-12f) / 448.0f;
+        scales[r] = scale;
+        for (int d = 0; d < D; ++d) {
+            volatile float y = row[d] / scale;
+            float c = y > 448.0f ? 448.0f : (y < -448.0f ? -448.0f : y);
+            codes[(int64_t)r * D + d] = encode_e4m3fn_rne(c);
+        }
+    }
+    return 0;
+}
+
+/* Round fp32 values to bf16 bit patterns (nearest, ties to even). */
+ORACLE_API int mfa_oracle_round_bf16(const float *x, int64_t n, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = encode_bf16_rne((double)x[i]);
+    return 0;
+}
+

@@ -196,3 +196,39 @@ def query_proj(x, w_qa, w_qb, eps, gain=None, want_f64=False):
         ctypes.c_int(r), ctypes.c_int(n_out), ctypes.c_double(eps), _ptr(q16), _ptr(q64), _ptr(ch))
     assert rc == 0, rc
     return (q16, q64, ch) if want_f64 else q16
+
+
+def linear(a, w):
+    """y = a . w in float64.  a: uint16 [B,K] (bf16 bit patterns) or float32 [B,K]; w: uint16 [K,N]."""
+    a = np.ascontiguousarray(a)
+    assert a.dtype in (np.uint16, np.float32)
+    w = _c(w, np.uint16)
+    B, K = a.shape
+    K2, N = w.shape
+    assert K2 == K
+    y = np.empty((B, N), dtype=np.float64)
+    rc = lib().mfa_oracle_linear(_ptr(a), ctypes.c_int(1 if a.dtype == np.float32 else 0), _ptr(w), ctypes.c_int(B),
+                                 ctypes.c_int(K), ctypes.c_int(N), _ptr(y))
+    assert rc == 0, rc
+    return y
+
+
+def quantize_rows_e4m3(x):
+    """Per-row e4m3fn quantisation in single precision: x float32 [rows, D] -> (codes uint8 [rows, D], scales float32 [rows])."""
+    x = _c(x, np.float32)
+    rows, D = x.shape
+    codes = np.empty((rows, D), dtype=np.uint8)
+    scales = np.empty((rows,), dtype=np.float32)
+    rc = lib().mfa_oracle_quantize_rows_e4m3(_ptr(x), ctypes.c_int(rows), ctypes.c_int(D), _ptr(codes), _ptr(scales))
+    assert rc == 0, rc
+    return codes, scales
+
+
+def round_bf16(x):
+    """float32 array -> bf16 bit patterns (uint16), nearest with ties to even."""
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    rc = lib().mfa_oracle_round_bf16(_ptr(x), ctypes.c_int64(x.size), _ptr(out))
+    assert rc == 0, rc
+    return out
+
