@@ -10,7 +10,8 @@ timed region; the cache is rotated over several distinct buffer sets so that the
 cache cannot serve it.
 
 --workload selects one of the other seeded workloads (ragged paged, long context, query path + fp8
-cache); they exist so that kernel profiles of those shapes can be taken with this same program.
+cache, the whole attention layer at the paper's 8K / 32K contexts); they exist so that kernel profiles of
+those shapes can be taken with this same program.
 
 Prints ONE JSON line: metric/value = KV tokens per second, plus
   roofline      HBM roofline of the streaming attention kernel from HIP-event timings taken in the timed region
@@ -121,6 +122,49 @@ def build_workload(key, mfa, W, n_sets):
         w.T, w.B = case.kv_tokens, B
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S)}
         w.keep = [x, w_qa, w_qb]
+    elif key in ("layer8k", "layer32k"):
+        # One whole attention layer of a decode step, the unit of the paper's attention-latency table
+        # (Section 7.3: 64 sequences per GPU, context 8K / 32K): query path, key/value projection of the
+        # new token and its cache record, attention over the lengthened cache, output projection.
+        S = 8192 if key == "layer8k" else 32768
+        B = 64
+        case = W.make_contiguous_case(key, 7, B=B, S=S, poison=False)
+        qc = W.make_query_proj_case(key + "_q", 5, B=B)
+        gen = torch.Generator().manual_seed(8)
+        w_kv = (torch.randn(W.D_MODEL, 2 * W.HEAD_DIM, generator=gen) * 0.02).to(torch.bfloat16)
+        w_o = (torch.randn(W.N_Q_HEADS * W.HEAD_DIM, W.D_MODEL, generator=gen) * 0.02).to(torch.bfloat16)
+        w.ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=S))
+        x = qc.x.cuda()
+        ks, vs = _roll_sets(case.k.cuda(), n_sets), _roll_sets(case.v.cuda(), n_sets)
+        # every layer of a model has its own weights: rotate them like the cache
+        wsets = [tuple(t.cuda() if j == 0 else t.cuda().clone() for t in (qc.w_qa, qc.w_qb, w_kv, w_o)) for j in range(n_sets)]
+        old_lens = torch.full((B,), S - 1, dtype=torch.int32, device="cuda")
+        new_lens = torch.full((B,), S, dtype=torch.int32, device="cuda")
+        q = torch.empty(B, 64, 256, dtype=torch.bfloat16, device="cuda")
+        out = torch.empty(B, 64, 256, dtype=torch.float32, device="cuda")
+        y = torch.empty(B, W.D_MODEL, dtype=torch.bfloat16, device="cuda")
+        attn = [mfa.PreparedDecodeAttn(w.ctx, q, ks[j], vs[j], new_lens, S, out) for j in range(n_sets)]
+
+        def step(j):
+            wa, wb, wkv, wo = wsets[j]
+            mfa.mfa_query_proj(w.ctx, x, wa, wb, q_out=q)
+            mfa.mfa_kv_append(w.ctx, x, wkv, ks[j], vs[j], old_lens)
+            attn[j]()
+            mfa.mfa_out_proj(w.ctx, out, wo, y=y)
+        w.steps = [(lambda j=j: step(j)) for j in range(n_sets)]
+        w.read_pairs = list(zip(ks, vs))
+        w.desc = ("attention layer of one decode step: B=64, query path 7168 -> 2048 -> 64x256, key/value projection "
+                  "7168 -> 2x256 + cache record, attention over ctx %d of contiguous bf16 KV, output projection "
+                  "16384 -> 7168; all weights bf16" % S)
+        w.metric = "KV tokens/s, MFA attention layer (linears + core attention), B=64, ctx %d, bf16, 1 GPU" % S
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<false>", 1024
+        w.T, w.B = B * S, B
+        w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S),
+                          "weight_bytes_per_step": 2 * (qc.w_qa.numel() + qc.w_qb.numel() + w_kv.numel() + w_o.numel()),
+                          "paper_layer_time_us": {"ctx": S, "H800": 281 if S == 8192 else 791, "H20": 438 if S == 8192 else 1452,
+                                                  "A800": 531 if S == 8192 else 1484,
+                                                  "note": "attention-latency table of Section 7.3 (their linears use 8-bit weights)"}}
+        w.keep = [x, wsets]
     else:
         raise ValueError(key)
     return w
@@ -131,7 +175,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5"), default="cfg2")
+    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "layer8k", "layer32k"), default="cfg2")
     ap.add_argument("--buffer-sets", type=int, default=None, help="distinct KV buffer sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")

@@ -116,6 +116,52 @@ MFA_API mfa_status mfa_query_proj(mfa_ctx* ctx, const void* x, const void* w_qa,
                           const void* w_qb, void* q_out, int32_t B, void* hip_stream);
 
 /*
+ * Key/value projection of the new token and its cache record (Section 6 counts both
+ * 7168 -> 256 projections in the attention layer and has the cache hold one key
+ * row and one value row per token, 8 bits per element in the deployed system):
+ *     [k_new | v_new] = x . W_kv                     [B, 2*head_dim], fp32 accumulation
+ *     bf16 cache: row seq_lens[b] of sequence b  <-  round-to-nearest-even(k_new), (v_new)
+ *     fp8 cache:  per token and tensor  scale = max(max_d |x_d|, 1e-12) / 448,
+ *                 code_d = e4m3(clamp(x_d / scale, -448, 448)),  scale stored beside the row;
+ *                 single precision throughout, so the codes depend on the fp32 row alone
+ *   x        bf16 [B, d_model]
+ *   w_kv     bf16 [d_model, 2*head_dim]  (in x out; key columns first, then value columns)
+ *   k_cache, v_cache, k_scale, v_scale, kv_seq_stride_tokens, seq_lens: as for
+ *            mfa_decode_attn, but written; seq_lens[b] is the number of tokens already
+ *            cached, i.e. the row the new token takes (the caller then attends with
+ *            seq_lens[b] + 1).  A row at or past kv_seq_stride_tokens is not written.
+ * The paper does not say where positional encoding enters; none is applied here.
+ */
+MFA_API mfa_status mfa_kv_append(mfa_ctx* ctx, const void* x, const void* w_kv, mfa_kv_dtype kv_dtype, void* k_cache,
+                         void* v_cache, float* k_scale, float* v_scale, int64_t kv_seq_stride_tokens,
+                         const int32_t* seq_lens, int32_t B, void* hip_stream);
+
+/* The same into a paged cache: the row is (seq_lens[b] % page_size) of page
+ * block_table[b][seq_lens[b] / page_size]; a block index at or past
+ * max_blocks_per_seq is not written. */
+MFA_API mfa_status mfa_kv_append_paged(mfa_ctx* ctx, const void* x, const void* w_kv, mfa_kv_dtype kv_dtype, void* k_pool,
+                               void* v_pool, float* k_scale_pool, float* v_scale_pool, int32_t n_pages,
+                               const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* seq_lens,
+                               int32_t B, void* hip_stream);
+
+/* Test aid: the record step alone from given fp32 rows kv [B, 2*head_dim] (block_table
+ * NULL: contiguous cache).  Used to check that rounding and quantisation are bit-exact. */
+MFA_API mfa_status mfa_debug_kv_record(mfa_ctx* ctx, const float* kv, mfa_kv_dtype kv_dtype, void* k_cache, void* v_cache,
+                               float* k_scale, float* v_scale, int64_t kv_seq_stride_tokens, const int32_t* block_table,
+                               int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t B, void* hip_stream);
+
+/*
+ * Output projection of the attention layer (Section 6: 64*256 -> 7168):
+ *     y = bf16(attn_out) . W_o
+ *   attn_out fp32 [B, n_q_heads*head_dim]   (what mfa_decode_attn* wrote)
+ *   w_o      bf16 [n_q_heads*head_dim, d_model]
+ *   y        bf16 [B, d_model]              (written)
+ * The attention output is rounded to bf16 for the MFMA, products accumulate in fp32,
+ * y is rounded to bf16 once on store.  1 <= B <= max_batch.
+ */
+MFA_API mfa_status mfa_out_proj(mfa_ctx* ctx, const float* attn_out, const void* w_o, void* y, int32_t B, void* hip_stream);
+
+/*
  * Decode-step attention over a contiguous cache (Section 2: 64 query heads
  * share one key head and one value head; Section 7.1: independent sequences):
  *     s[b,h,j] = softmax_scale * sum_d q[b,h,d] * K[b,j,d]        j < seq_lens[b]

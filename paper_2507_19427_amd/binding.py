@@ -26,6 +26,7 @@ EXPORTS = [
     "mfa_decode_workspace_bytes", "mfa_decode_init", "mfa_decode_destroy", "mfa_status_string",
     "mfa_query_proj", "mfa_decode_attn", "mfa_decode_attn_paged", "mfa_debug_gather_paged",
     "mfa_decode_num_splits", "mfa_debug_set_kernel_events", "mfa_debug_stream_read",
+    "mfa_kv_append", "mfa_kv_append_paged", "mfa_debug_kv_record", "mfa_out_proj",
 ]
 
 
@@ -96,6 +97,14 @@ def lib():
     L.mfa_debug_stream_read.argtypes = [vp, vp, vp, sz, vp]
     L.mfa_decode_num_splits.restype = i32
     L.mfa_decode_num_splits.argtypes = [vp, i32, i32]
+    L.mfa_kv_append.restype = ctypes.c_int
+    L.mfa_kv_append.argtypes = [vp, vp, vp, ctypes.c_int, vp, vp, vp, vp, i64, vp, i32, vp]
+    L.mfa_kv_append_paged.restype = ctypes.c_int
+    L.mfa_kv_append_paged.argtypes = [vp, vp, vp, ctypes.c_int, vp, vp, vp, vp, i32, vp, i32, vp, i32, vp]
+    L.mfa_debug_kv_record.restype = ctypes.c_int
+    L.mfa_debug_kv_record.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, vp, i64, vp, i32, vp, i32, vp]
+    L.mfa_out_proj.restype = ctypes.c_int
+    L.mfa_out_proj.argtypes = [vp, vp, vp, vp, i32, vp]
     _lib = L
     return L
 
@@ -281,6 +290,82 @@ def mfa_debug_stream_read(ctx: MfaContext, a, b):
     if b.numel() * b.element_size() != nbytes:
         raise ValueError("buffers must have equal size")
     _check(lib().mfa_debug_stream_read(ctx.handle, _ptr(a), _ptr(b), nbytes, _stream()), "mfa_debug_stream_read")
+
+
+def _check_cache_pair(k, v, ks, vs, rows_shape):
+    kvd = _kv_dtype(k)
+    if v.dtype != k.dtype or not k.is_contiguous() or not v.is_contiguous() or tuple(v.shape) != tuple(k.shape):
+        raise TypeError("key and value caches must be contiguous, of one dtype and one shape")
+    for t, nm in ((ks, "k_scale"), (vs, "v_scale")):
+        if t is not None:
+            _want(t, torch.float32, nm)
+            if tuple(t.shape) != tuple(rows_shape):
+                raise ValueError(nm + " shape")
+    return kvd
+
+
+def mfa_kv_append(ctx: MfaContext, x, w_kv, k_cache, v_cache, seq_lens, k_scale=None, v_scale=None):
+    """x bf16 [B,d_model], w_kv bf16 [d_model, 2*head_dim]; writes row seq_lens[b] of k_cache/v_cache [B,S,D]."""
+    cfg = ctx.cfg
+    _want(x, torch.bfloat16, "x")
+    _want(w_kv, torch.bfloat16, "w_kv")
+    _want(seq_lens, torch.int32, "seq_lens")
+    B = x.shape[0]
+    if tuple(x.shape) != (B, cfg.d_model) or tuple(w_kv.shape) != (cfg.d_model, 2 * cfg.head_dim) or \
+            k_cache.dim() != 3 or k_cache.shape[0] != B or k_cache.shape[2] != cfg.head_dim or tuple(seq_lens.shape) != (B,):
+        raise ValueError("kv append shapes do not match")
+    kvd = _check_cache_pair(k_cache, v_cache, k_scale, v_scale, k_cache.shape[:2])
+    _check(lib().mfa_kv_append(ctx.handle, _ptr(x), _ptr(w_kv), kvd, _ptr(k_cache), _ptr(v_cache), _ptr(k_scale),
+                               _ptr(v_scale), k_cache.shape[1], _ptr(seq_lens), B, _stream()), "mfa_kv_append")
+
+
+def mfa_kv_append_paged(ctx: MfaContext, x, w_kv, k_pool, v_pool, block_table, seq_lens, k_scale_pool=None,
+                        v_scale_pool=None):
+    """The same into pools [n_pages,page,D] behind block_table int32 [B,max_blocks]."""
+    cfg = ctx.cfg
+    _want(x, torch.bfloat16, "x")
+    _want(w_kv, torch.bfloat16, "w_kv")
+    _want(seq_lens, torch.int32, "seq_lens")
+    _want(block_table, torch.int32, "block_table")
+    B = x.shape[0]
+    n_pages = k_pool.shape[0]
+    if tuple(x.shape) != (B, cfg.d_model) or tuple(w_kv.shape) != (cfg.d_model, 2 * cfg.head_dim) or \
+            tuple(k_pool.shape) != (n_pages, cfg.page_size, cfg.head_dim) or block_table.shape[0] != B or \
+            tuple(seq_lens.shape) != (B,):
+        raise ValueError("paged kv append shapes do not match")
+    kvd = _check_cache_pair(k_pool, v_pool, k_scale_pool, v_scale_pool, k_pool.shape[:2])
+    _check(lib().mfa_kv_append_paged(ctx.handle, _ptr(x), _ptr(w_kv), kvd, _ptr(k_pool), _ptr(v_pool), _ptr(k_scale_pool),
+                                     _ptr(v_scale_pool), n_pages, _ptr(block_table), block_table.shape[1], _ptr(seq_lens),
+                                     B, _stream()), "mfa_kv_append_paged")
+
+
+def mfa_debug_kv_record(ctx: MfaContext, kv, k_cache, v_cache, seq_lens, k_scale=None, v_scale=None, block_table=None):
+    """Write given fp32 rows kv [B, 2*head_dim] as the new token's record (contiguous [B,S,D] or pools + block_table)."""
+    _want(kv, torch.float32, "kv")
+    _want(seq_lens, torch.int32, "seq_lens")
+    B = kv.shape[0]
+    kvd = _check_cache_pair(k_cache, v_cache, k_scale, v_scale, k_cache.shape[:2])
+    stride = 0 if block_table is not None else k_cache.shape[1]
+    width = block_table.shape[1] if block_table is not None else 0
+    _check(lib().mfa_debug_kv_record(ctx.handle, _ptr(kv), kvd, _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
+                                     stride, _ptr(block_table), width, _ptr(seq_lens), B, _stream()), "mfa_debug_kv_record")
+
+
+def mfa_out_proj(ctx: MfaContext, attn_out, w_o, y=None):
+    """attn_out fp32 [B,H,D] (or [B,H*D]), w_o bf16 [H*D, d_model] -> y bf16 [B, d_model]."""
+    cfg = ctx.cfg
+    _want(attn_out, torch.float32, "attn_out")
+    _want(w_o, torch.bfloat16, "w_o")
+    B = attn_out.shape[0]
+    n_in = cfg.n_q_heads * cfg.head_dim
+    if attn_out.numel() != B * n_in or tuple(w_o.shape) != (n_in, cfg.d_model):
+        raise ValueError("output projection shapes do not match")
+    if y is None:
+        y = torch.empty(B, cfg.d_model, dtype=torch.bfloat16, device=attn_out.device)
+    else:
+        _want(y, torch.bfloat16, "y")
+    _check(lib().mfa_out_proj(ctx.handle, _ptr(attn_out), _ptr(w_o), _ptr(y), B, _stream()), "mfa_out_proj")
+    return y
 
 
 class PreparedDecodeAttn:

@@ -89,8 +89,16 @@ Carve carve(const mfa_config* c, int32_t target)
     w.acc = off; off = align_up(off + w.max_items * kPartialAccFloats * sizeof(float), 256);
     w.ml = off;  off = align_up(off + w.max_items * kPartialMlFloats * sizeof(float), 256);
     w.seg = off; off = align_up(off + (size_t)c->max_batch * 2 * sizeof(int32_t), 256);
-    w.c = off;   off = align_up(off + (size_t)w.qproj.split_k * w.rows_pad * c->q_rank * sizeof(float), 256);
-    w.chat = off; off = align_up(off + (size_t)w.rows_pad * c->q_rank * 2, 256);
+    // split-K partials of whichever product is running, and the bf16 k-step-major activations of the
+    // second query product / the output projection
+    const int32_t n_attn = c->n_q_heads * c->head_dim;
+    size_t partial_floats = (size_t)w.qproj.split_k * c->q_rank;
+    const size_t kv_floats = (size_t)plan_linear(c->d_model, kKvWidth).split_k * kKvWidth;
+    const size_t o_floats = (size_t)plan_linear(n_attn, c->d_model).split_k * c->d_model;
+    if (kv_floats > partial_floats) partial_floats = kv_floats;
+    if (o_floats > partial_floats) partial_floats = o_floats;
+    w.c = off;   off = align_up(off + partial_floats * w.rows_pad * sizeof(float), 256);
+    w.chat = off; off = align_up(off + (size_t)w.rows_pad * (c->q_rank > n_attn ? c->q_rank : n_attn) * 2, 256);
     w.total = off;
     return w;
 }
@@ -245,6 +253,90 @@ mfa_status mfa_query_proj(mfa_ctx* ctx, const void* x, const void* w_qa, const f
     a.k_per_split = ctx->qproj.k_per_split;
     a.eps = ctx->cfg.rms_eps;
     return launch_query_proj(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+namespace {
+
+mfa_status check_kv_append(const mfa_ctx* ctx, const void* x, const void* w_kv, mfa_kv_dtype kv_dtype, const void* k,
+                           const void* v, const float* ks, const float* vs, const int32_t* seq_lens, int32_t B)
+{
+    if (!ctx || !x || !w_kv || !k || !v || !seq_lens) return MFA_ERR_INVALID_ARG;
+    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return MFA_ERR_INVALID_ARG;
+    if (kv_dtype == MFA_KV_FP8_E4M3 && (!ks || !vs)) return MFA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_kv) || !aligned16(k) || !aligned16(v) || !aligned16(ks) || !aligned16(vs) ||
+        (reinterpret_cast<uintptr_t>(seq_lens) & 3u))
+        return MFA_ERR_INVALID_ARG;
+    if (B < 1 || B > ctx->cfg.max_batch) return MFA_ERR_INVALID_ARG;
+    if (!on_device(ctx)) return MFA_ERR_INVALID_ARG;
+    return MFA_OK;
+}
+
+void fill_kv_append(const mfa_ctx* ctx, KvAppendArgs& a, const void* x, const void* w_kv, void* k, void* v, float* ks,
+                    float* vs, const int32_t* seq_lens, int32_t B)
+{
+    a.x = x; a.w_kv = w_kv; a.k = k; a.v = v; a.k_scale = ks; a.v_scale = vs; a.seq_lens = seq_lens;
+    a.block_table = nullptr; a.ws_c = ctx->ws_c; a.seq_stride_tokens = 0; a.max_blocks_per_seq = 0;
+    a.B = B; a.d_model = ctx->cfg.d_model;
+    a.plan = plan_linear(ctx->cfg.d_model, kKvWidth);
+}
+
+}  // namespace
+
+mfa_status mfa_kv_append(mfa_ctx* ctx, const void* x, const void* w_kv, mfa_kv_dtype kv_dtype, void* k_cache,
+                         void* v_cache, float* k_scale, float* v_scale, int64_t kv_seq_stride_tokens,
+                         const int32_t* seq_lens, int32_t B, void* hip_stream)
+{
+    const mfa_status st = check_kv_append(ctx, x, w_kv, kv_dtype, k_cache, v_cache, k_scale, v_scale, seq_lens, B);
+    if (st != MFA_OK) return st;
+    if (kv_seq_stride_tokens < 1) return MFA_ERR_INVALID_ARG;
+    KvAppendArgs a{};
+    fill_kv_append(ctx, a, x, w_kv, k_cache, v_cache, k_scale, v_scale, seq_lens, B);
+    a.seq_stride_tokens = kv_seq_stride_tokens;
+    return launch_kv_append(a, kv_dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+mfa_status mfa_kv_append_paged(mfa_ctx* ctx, const void* x, const void* w_kv, mfa_kv_dtype kv_dtype, void* k_pool,
+                               void* v_pool, float* k_scale_pool, float* v_scale_pool, int32_t n_pages,
+                               const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* seq_lens,
+                               int32_t B, void* hip_stream)
+{
+    const mfa_status st = check_kv_append(ctx, x, w_kv, kv_dtype, k_pool, v_pool, k_scale_pool, v_scale_pool, seq_lens, B);
+    if (st != MFA_OK) return st;
+    if (!block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u) || n_pages < 1 || max_blocks_per_seq < 1)
+        return MFA_ERR_INVALID_ARG;
+    KvAppendArgs a{};
+    fill_kv_append(ctx, a, x, w_kv, k_pool, v_pool, k_scale_pool, v_scale_pool, seq_lens, B);
+    a.block_table = block_table;
+    a.max_blocks_per_seq = max_blocks_per_seq;
+    return launch_kv_append(a, kv_dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+mfa_status mfa_debug_kv_record(mfa_ctx* ctx, const float* kv, mfa_kv_dtype kv_dtype, void* k_cache, void* v_cache,
+                               float* k_scale, float* v_scale, int64_t kv_seq_stride_tokens, const int32_t* block_table,
+                               int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t B, void* hip_stream)
+{
+    const mfa_status st = check_kv_append(ctx, kv, kv, kv_dtype, k_cache, v_cache, k_scale, v_scale, seq_lens, B);
+    if (st != MFA_OK) return st;
+    if (block_table ? max_blocks_per_seq < 1 : kv_seq_stride_tokens < 1) return MFA_ERR_INVALID_ARG;
+    KvAppendArgs a{};
+    fill_kv_append(ctx, a, nullptr, nullptr, k_cache, v_cache, k_scale, v_scale, seq_lens, B);
+    a.block_table = block_table;
+    a.max_blocks_per_seq = max_blocks_per_seq;
+    a.seq_stride_tokens = kv_seq_stride_tokens;
+    return launch_kv_record(a, kv, kv_dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+mfa_status mfa_out_proj(mfa_ctx* ctx, const float* attn_out, const void* w_o, void* y, int32_t B, void* hip_stream)
+{
+    if (!ctx || !attn_out || !w_o || !y) return MFA_ERR_INVALID_ARG;
+    if (!aligned16(attn_out) || !aligned16(w_o) || !aligned16(y)) return MFA_ERR_INVALID_ARG;
+    if (B < 1 || B > ctx->cfg.max_batch) return MFA_ERR_INVALID_ARG;
+    if (!on_device(ctx)) return MFA_ERR_INVALID_ARG;
+    OutProjArgs a{};
+    a.attn = attn_out; a.w_o = w_o; a.y = y; a.ws_c = ctx->ws_c; a.ws_act = ctx->ws_chat;
+    a.B = B; a.n_in = ctx->cfg.n_q_heads * ctx->cfg.head_dim; a.d_model = ctx->cfg.d_model;
+    a.plan = plan_linear(a.n_in, a.d_model);
+    return launch_out_proj(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }
 
 mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,

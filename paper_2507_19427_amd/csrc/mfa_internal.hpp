@@ -82,12 +82,48 @@ struct QProjArgs {
 };
 constexpr int kQProjRows = 128;   // rows of x one workgroup covers
 struct QProjPlan {
-    int32_t split_k;      // K splits of the first product (fp32 partials in the workspace)
+    int32_t split_k;      // K splits of a product whose fp32 partials go through the workspace
     int32_t k_per_split;
 };
-QProjPlan plan_qproj(int32_t d_model, int32_t q_rank);
+// Split of the k range of y = x.W ([K] -> [N]) that fills the device: N/64 column strips times split_k
+// workgroups, about one per compute unit, at most 32 splits.
+QProjPlan plan_linear(int32_t K, int32_t N);
+inline QProjPlan plan_qproj(int32_t d_model, int32_t q_rank) { return plan_linear(d_model, q_rank); }
 hipError_t prepare_query_proj_kernels();   // one-time function attributes (dynamic LDS size)
 hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream);
+
+// Key/value projection of the new token and its cache record.
+constexpr int kKvWidth = 2 * kHeadDim;     // columns of W_kv: key then value
+struct KvAppendArgs {
+    const void* x;                 // bf16 [B, d_model]
+    const void* w_kv;              // bf16 [d_model, 512]
+    void* k;                       // cache or pool (bf16 or e4m3 codes)
+    void* v;
+    float* k_scale;                // fp8 only
+    float* v_scale;
+    const int32_t* seq_lens;       // device: tokens already cached = row the new token takes
+    const int32_t* block_table;    // device, NULL for contiguous
+    float* ws_c;                   // fp32 [split_k][B_pad][512]
+    int64_t seq_stride_tokens;     // contiguous only
+    int32_t max_blocks_per_seq;    // paged only
+    int32_t B, d_model;
+    QProjPlan plan;
+};
+hipError_t launch_kv_append(const KvAppendArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream);
+// The record step alone, from given fp32 rows kv [B, 512] (plan.split_k is ignored: one "partial").
+hipError_t launch_kv_record(const KvAppendArgs& a, const float* kv, mfa_kv_dtype kv_dtype, hipStream_t stream);
+
+// Output projection y = bf16(attn) . W_o.
+struct OutProjArgs {
+    const float* attn;             // fp32 [B, n_in]
+    const void* w_o;               // bf16 [n_in, d_model]
+    void* y;                       // bf16 [B, d_model]
+    float* ws_c;                   // fp32 [split_k][B_pad][d_model]
+    void* ws_act;                  // bf16 k-step-major copy of attn
+    int32_t B, n_in, d_model;
+    QProjPlan plan;
+};
+hipError_t launch_out_proj(const OutProjArgs& a, hipStream_t stream);
 
 hipError_t launch_gather_paged(const void* pool, int32_t row_bytes, const int32_t* block_table,
                                int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t max_seq_len_hint,

@@ -40,7 +40,9 @@ __device__ __forceinline__ int w_key(int row) { return (((row >> 3) & 1) << 1) |
 // X_TILED = false: x is row-major [M, K].
 // X_TILED = true : x is stored k-step-major, element (m, k) at ((k/32)*rows_pad + m)*32 + k%32, so
 //                  that the 16 rows x 64 B a wave loads per k step are contiguous.
-template <bool OUT_BF16, bool X_TILED>
+// MB = 2 or 1: 16-row blocks per wave; a workgroup covers 64 * MB rows of x (MB = 1 when there are
+//                  no more than 64 rows: half the x traffic and MFMA work).
+template <bool OUT_BF16, bool X_TILED, int MB>
 __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_t* __restrict__ X,
                                                                    const uint16_t* __restrict__ W,
                                                                    void* __restrict__ out, int M, int K, int N,
@@ -52,13 +54,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int mp = wave & 3;                  // rows 32*mp .. 32*mp+31 of the 128-row tile
+    const int mp = wave & 3;                  // rows 16*MB*mp .. of the workgroup's tile
     const int kh = wave >> 2;                 // takes the k steps of every stage with (step & 1) == kh
     const int n = lane & 15;
     const int g = lane >> 4;
 
     const int n0 = blockIdx.x * kStripN;
-    const int m0 = blockIdx.y * kQProjRows;
+    const int m0 = blockIdx.y * 64 * MB;
     const int kz = blockIdx.z;
     const int k_begin = kz * k_per_split;
     const int k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
@@ -85,11 +87,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
     // holds x[row][k0 + 32*(2j + kh) + 8g .. +7].  Every x element is loaded by exactly one wave.
     // Two sets: the next stage's fragments are requested right after its W, a whole stage ahead.
     constexpr int kMySteps = kStepsPerStage / 2;
-    bf16x8 xf[2][2][kMySteps];                // [buffer][row block][own k step]
-    int xrow[2];
+    bf16x8 xf[2][MB][kMySteps];               // [buffer][row block][own k step]
+    int xrow[MB];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-        const int r = m0 + 32 * mp + 16 * mb + n;
+    for (int mb = 0; mb < MB; ++mb) {
+        const int r = m0 + 16 * MB * mp + 16 * mb + n;
         xrow[mb] = r < M ? r : M - 1;         // rows past M repeat the last one; their results are not stored
     }
     auto load_x_stage = [&](int stage, int buf) {
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
             int k = k0 + 32 * (2 * j + kh) + 8 * g;
             k = k + 8 <= K ? k : K - 8;       // steps past k_end are never used; keep the address inside x
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
+            for (int mb = 0; mb < MB; ++mb) {
                 const size_t idx = X_TILED ? ((size_t)(k >> 5) * rows_pad + xrow[mb]) * 32 + (k & 31)
                                            : (size_t)xrow[mb] * K + k;
                 xf[buf][mb][j] = *(const bf16x8*)(X + idx);
@@ -107,9 +109,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
         }
     };
 
-    f32x4 acc[2][kColBlocks];
+    f32x4 acc[MB][kColBlocks];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < kColBlocks; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
@@ -127,12 +129,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
                 f.nb[nb].h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
             }
     };
-    auto multiply = [&](const AFrag& f, const bf16x8& x0, const bf16x8& x1) {
+    auto multiply = [&](const AFrag& f, int buf, int j) {
 #pragma unroll
-        for (int nb = 0; nb < kColBlocks; ++nb) {
-            acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.nb[nb].v, x0, acc[0][nb], 0, 0, 0);
-            acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.nb[nb].v, x1, acc[1][nb], 0, 0, 0);
-        }
+        for (int nb = 0; nb < kColBlocks; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.nb[nb].v, xf[buf][mb][j], acc[mb][nb], 0, 0, 0);
     };
     // The A operands of the next own step are read from LDS while the current one is multiplied, so
     // that the LDS latency hides behind eight MFMAs instead of stalling each pair.
@@ -148,11 +150,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
             for (int j = 0; j < kMySteps; j += 2) {
                 read_a(fb, base, 2 * (j + 1) + kh);
                 __builtin_amdgcn_sched_barrier(0);
-                multiply(fa, xf[buf][0][j], xf[buf][1][j]);
+                multiply(fa, buf, j);
                 __builtin_amdgcn_sched_barrier(0);
                 if (j + 2 < kMySteps) read_a(fa, base, 2 * (j + 2) + kh);
                 __builtin_amdgcn_sched_barrier(0);
-                multiply(fb, xf[buf][0][j + 1], xf[buf][1][j + 1]);
+                multiply(fb, buf, j + 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
             for (int j = 0; j < kMySteps; ++j)
                 if (2 * j + kh < steps) {
                     read_a(fa, base, 2 * j + kh);
-                    multiply(fa, xf[buf][0][j], xf[buf][1][j]);
+                    multiply(fa, buf, j);
                 }
         }
     };
@@ -195,10 +197,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
     __syncthreads();
     {
         constexpr int kHalf = kColBlocks / 2;
-        const int mine = (mp * 2 + kh) * 2 * kHalf;   // slots of 1 KB: [row block][kHalf column blocks]
-        const int theirs = (mp * 2 + (kh ^ 1)) * 2 * kHalf;
+        const int mine = (mp * 2 + kh) * MB * kHalf;  // slots of 1 KB: [row block][kHalf column blocks]
+        const int theirs = (mp * 2 + (kh ^ 1)) * MB * kHalf;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int j = 0; j < kHalf; ++j) {
                 const f32x4 v = kh == 0 ? acc[mb][kHalf + j] : acc[mb][j];
@@ -206,8 +208,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
             }
         __syncthreads();
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            const int m = m0 + 32 * mp + 16 * mb + n;
+        for (int mb = 0; mb < MB; ++mb) {
+            const int m = m0 + 16 * MB * mp + 16 * mb + n;
 #pragma unroll
             for (int j = 0; j < kHalf; ++j) {
                 const f32x4 other = *LDS_AT(f32x4, lds_base, (theirs + mb * kHalf + j) * 1024 + lane * 16);
@@ -273,15 +275,127 @@ __global__ __launch_bounds__(256) void rmsnorm_reduce_kernel(const float* __rest
     }
 }
 
+// ---- the new token's cache record (Section 6: the cache holds one key row and one value row per
+// token, 8 bits per element in the deployed system).
+// One workgroup per sequence, thread t owns key element t and value element t.  The fp32 rows are the
+// sum of the projection's split-K partials in split order.  bf16 cache: round to nearest even.
+// fp8 cache: per token and tensor scale = max(max|x|, 1e-12) / 448 and code = e4m3(x / scale), the
+// quotient clamped to +-448; all in single precision with correctly rounded divisions, so that the
+// codes are a function of the fp32 row alone.  The row written is seq_lens[b] (the tokens already
+// cached); a row outside the cache or the block table is not written.
+template <bool FP8, bool PAGED>
+__global__ __launch_bounds__(kHeadDim) void kv_record_kernel(const float* __restrict__ parts, int split_k, int rows_pad,
+                                                             KvAppendArgs a)
+{
+    __shared__ float red[2][kHeadDim / 64];
+    const int b = blockIdx.x;
+    const int t = threadIdx.x;
+    float kx = 0.f, vx = 0.f;
+    for (int z0 = 0; z0 < split_k; z0 += 8) {           // eight splits' loads in flight together, summed in split order
+        float kp[8], vp[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int z = z0 + u < split_k ? z0 + u : split_k - 1;
+            const float* row = parts + ((size_t)z * rows_pad + b) * kKvWidth;
+            kp[u] = row[t];
+            vp[u] = row[kHeadDim + t];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (z0 + u < split_k) { kx += kp[u]; vx += vp[u]; }
+    }
+    const int pos = a.seq_lens[b];
+    int64_t row;
+    if (PAGED) {
+        const int blk = pos / kPage;
+        if (pos < 0 || blk >= a.max_blocks_per_seq) return;
+        row = (int64_t)a.block_table[(size_t)b * a.max_blocks_per_seq + blk] * kPage + pos % kPage;
+    } else {
+        if (pos < 0 || pos >= a.seq_stride_tokens) return;
+        row = (int64_t)b * a.seq_stride_tokens + pos;
+    }
+    if (!FP8) {
+        ((__bf16*)a.k)[row * kHeadDim + t] = (__bf16)kx;
+        ((__bf16*)a.v)[row * kHeadDim + t] = (__bf16)vx;
+        return;
+    }
+    float ka = fabsf(kx), va = fabsf(vx);
+    for (int off = 32; off > 0; off >>= 1) {
+        ka = fmaxf(ka, __shfl_xor(ka, off));
+        va = fmaxf(va, __shfl_xor(va, off));
+    }
+    if ((t & 63) == 0) { red[0][t >> 6] = ka; red[1][t >> 6] = va; }
+    __syncthreads();
+    ka = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+    va = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+    const float ks = fmaxf(ka, 1e-12f) / 448.0f;
+    const float vs = fmaxf(va, 1e-12f) / 448.0f;
+    const float ky = fminf(fmaxf(kx / ks, -448.0f), 448.0f);
+    const float vy = fminf(fmaxf(vx / vs, -448.0f), 448.0f);
+    ((uint8_t*)a.k)[row * kHeadDim + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(ky, 0.f, 0, false) & 0xFF);
+    ((uint8_t*)a.v)[row * kHeadDim + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(vy, 0.f, 0, false) & 0xFF);
+    if (t == 0) { a.k_scale[row] = ks; a.v_scale[row] = vs; }
+}
+static_assert(kHeadDim == 256, "kv_record_kernel reduces over four waves");
+
+// fp32 [M, K] -> bf16, k-step-major: element (m, k) at ((k/32)*rows_pad + m)*32 + k%32.
+__global__ __launch_bounds__(256) void to_bf16_tiled_kernel(const float* __restrict__ src, __bf16* __restrict__ dst, int M, int K,
+                                                            int rows_pad)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;          // over M * K / 4
+    if (i >= (size_t)M * K / 4) return;
+    const int m = (int)(i / (K / 4));
+    const int k = (int)(i % (K / 4)) * 4;
+    const f32x4 v = *(const f32x4*)(src + (size_t)m * K + k);
+    union { __bf16 h[4]; uint2 u; } o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o.h[j] = (__bf16)v[j];
+    *(uint2*)(dst + ((size_t)(k >> 5) * rows_pad + m) * 32 + (k & 31)) = o.u;
+}
+
+// y[m][n] = bf16(sum over splits, in split order, of the fp32 partials).
+__global__ __launch_bounds__(256) void reduce_partials_bf16_kernel(const float* __restrict__ parts, __bf16* __restrict__ y, int M, int N,
+                                                                   int split_k, int rows_pad)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;          // over M * N / 4
+    if (i >= (size_t)M * N / 4) return;
+    const int m = (int)(i / (N / 4));
+    const int n = (int)(i % (N / 4)) * 4;
+    f32x4 c = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < split_k; ++z) c += *(const f32x4*)(parts + ((size_t)z * rows_pad + m) * N + n);
+    union { __bf16 h[4]; uint2 u; } o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o.h[j] = (__bf16)c[j];
+    *(uint2*)(y + (size_t)m * N + n) = o.u;
+}
+
 }  // namespace
 
-QProjPlan plan_qproj(int32_t d_model, int32_t q_rank)
+namespace {
+
+// One streaming product: rows of x in tiles of 128 (64 when there are no more), strips of 64 columns, k splits.
+template <bool OUT_BF16, bool X_TILED>
+hipError_t launch_gemm(const void* X, const void* Wt, void* out, int M, int K, int N, const QProjPlan& plan, int split_k,
+                       int rows_pad, hipStream_t stream)
 {
-    const int32_t strips = q_rank / kStripN;
+    if (M <= 64)
+        hipLaunchKernelGGL((gemm_stream_kernel<OUT_BF16, X_TILED, 1>), dim3(N / kStripN, 1, split_k), dim3(kGemmThreads), kGemmLdsBytes,
+                           stream, (const uint16_t*)X, (const uint16_t*)Wt, out, M, K, N, plan.k_per_split, rows_pad);
+    else
+        hipLaunchKernelGGL((gemm_stream_kernel<OUT_BF16, X_TILED, 2>), dim3(N / kStripN, (M + 127) / 128, split_k), dim3(kGemmThreads),
+                           kGemmLdsBytes, stream, (const uint16_t*)X, (const uint16_t*)Wt, out, M, K, N, plan.k_per_split, rows_pad);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+QProjPlan plan_linear(int32_t K, int32_t N)
+{
+    const int32_t strips = N / kStripN;
     int32_t want = 256 / (strips > 0 ? strips : 1);
     if (want < 1) want = 1;
-    if (want > 16) want = 16;
-    const int32_t ksteps = d_model / 32;
+    if (want > 32) want = 32;
+    const int32_t ksteps = K / 32;
     const int32_t per = (ksteps + want - 1) / want;
     QProjPlan p;
     p.k_per_split = per * 32;
@@ -291,27 +405,75 @@ QProjPlan plan_qproj(int32_t d_model, int32_t q_rank)
 
 hipError_t prepare_query_proj_kernels()
 {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_stream_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void*)gemm_stream_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    const void* kernels[] = {(const void*)gemm_stream_kernel<false, false, 1>, (const void*)gemm_stream_kernel<false, false, 2>,
+                             (const void*)gemm_stream_kernel<true, true, 1>, (const void*)gemm_stream_kernel<true, true, 2>,
+                             (const void*)gemm_stream_kernel<false, true, 1>, (const void*)gemm_stream_kernel<false, true, 2>};
+    for (const void* k : kernels) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream)
 {
     const int m_blocks = (a.B + kQProjRows - 1) / kQProjRows;
     const int rows_pad = m_blocks * kQProjRows;
-    hipLaunchKernelGGL((gemm_stream_kernel<false, false>), dim3(a.q_rank / kStripN, m_blocks, a.split_k), dim3(kGemmThreads),
-                       kGemmLdsBytes, stream, (const uint16_t*)a.x, (const uint16_t*)a.w_qa, (void*)a.ws_c, a.B,
-                       a.d_model, a.q_rank, a.k_per_split, rows_pad);
-    hipError_t e = hipGetLastError();
+    QProjPlan plan;
+    plan.split_k = a.split_k;
+    plan.k_per_split = a.k_per_split;
+    hipError_t e = launch_gemm<false, false>(a.x, a.w_qa, a.ws_c, a.B, a.d_model, a.q_rank, plan, a.split_k, rows_pad, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(rmsnorm_reduce_kernel, dim3(a.B), dim3(256), a.q_rank * sizeof(float), stream,
                        (const float*)a.ws_c, a.gain, (__bf16*)a.ws_chat, a.q_rank, a.split_k, rows_pad, a.eps);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemm_stream_kernel<true, true>), dim3(a.n_out / kStripN, m_blocks, 1), dim3(kGemmThreads),
-                       kGemmLdsBytes, stream, (const uint16_t*)a.ws_chat, (const uint16_t*)a.w_qb, a.q_out, a.B,
-                       a.q_rank, a.n_out, a.q_rank, rows_pad);
+    plan.split_k = 1;
+    plan.k_per_split = a.q_rank;
+    return launch_gemm<true, true>(a.ws_chat, a.w_qb, a.q_out, a.B, a.q_rank, a.n_out, plan, 1, rows_pad, stream);
+}
+
+namespace {
+
+template <bool FP8>
+hipError_t launch_record(const KvAppendArgs& a, const float* parts, int split_k, int rows_pad, hipStream_t stream)
+{
+    if (a.block_table) hipLaunchKernelGGL((kv_record_kernel<FP8, true>), dim3(a.B), dim3(kHeadDim), 0, stream, parts, split_k, rows_pad, a);
+    else               hipLaunchKernelGGL((kv_record_kernel<FP8, false>), dim3(a.B), dim3(kHeadDim), 0, stream, parts, split_k, rows_pad, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_kv_record(const KvAppendArgs& a, const float* kv, mfa_kv_dtype kv_dtype, hipStream_t stream)
+{
+    return kv_dtype == MFA_KV_FP8_E4M3 ? launch_record<true>(a, kv, 1, a.B, stream) : launch_record<false>(a, kv, 1, a.B, stream);
+}
+
+hipError_t launch_kv_append(const KvAppendArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream)
+{
+    const int m_blocks = (a.B + kQProjRows - 1) / kQProjRows;
+    const int rows_pad = m_blocks * kQProjRows;
+    const hipError_t e = launch_gemm<false, false>(a.x, a.w_kv, a.ws_c, a.B, a.d_model, kKvWidth, a.plan, a.plan.split_k, rows_pad, stream);
+    if (e != hipSuccess) return e;
+    return kv_dtype == MFA_KV_FP8_E4M3 ? launch_record<true>(a, a.ws_c, a.plan.split_k, rows_pad, stream)
+                                       : launch_record<false>(a, a.ws_c, a.plan.split_k, rows_pad, stream);
+}
+
+hipError_t launch_out_proj(const OutProjArgs& a, hipStream_t stream)
+{
+    const int m_blocks = (a.B + kQProjRows - 1) / kQProjRows;
+    const int rows_pad = m_blocks * kQProjRows;
+    const size_t n4 = (size_t)a.B * a.n_in / 4;
+    hipLaunchKernelGGL(to_bf16_tiled_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, a.attn, (__bf16*)a.ws_act,
+                       a.B, a.n_in, rows_pad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_gemm<false, true>(a.ws_act, a.w_o, a.ws_c, a.B, a.n_in, a.d_model, a.plan, a.plan.split_k, rows_pad, stream);
+    if (e != hipSuccess) return e;
+    const size_t o4 = (size_t)a.B * a.d_model / 4;
+    hipLaunchKernelGGL(reduce_partials_bf16_kernel, dim3((unsigned)((o4 + 255) / 256)), dim3(256), 0, stream, (const float*)a.ws_c,
+                       (__bf16*)a.y, a.B, a.d_model, a.plan.split_k, rows_pad);
     return hipGetLastError();
 }
 
