@@ -43,3 +43,33 @@ def attn_linear_weight_bytes_per_gpu(d_model, q_rank, n_q_heads, head_dim, bytes
 def arithmetic_intensity(n_q_heads, head_dim, bytes_per_elem):
     """Attention flops per cache byte: 4*H*D flop over 2*D*bytes per cached token."""
     return 4 * n_q_heads * head_dim / kv_bytes_per_token_per_layer(head_dim, bytes_per_elem)
+
+
+# ---------------------------------------------------------------------------
+# The paper's theoretical decoding cost of the attention part (Section 4.2):
+# the larger of the core's computation cost and its cache-access cost, plus the
+# computation cost of the linears before and after, each priced by the
+# accelerator's cost per flop and per byte of memory access.
+# ---------------------------------------------------------------------------
+
+def unit_costs(price_per_hour, peak_flops, peak_bytes_per_s):
+    """(cost per flop, cost per byte) of an accelerator rented at price_per_hour and fully used."""
+    per_second = price_per_hour / 3600.0
+    return per_second / peak_flops, per_second / peak_bytes_per_s
+
+
+def attention_cost_per_token(attn_flops, kv_bytes, linear_flops, cost_per_flop, cost_per_byte):
+    """max(flop cost of the attention core, byte cost of its cache reads) + flop cost of the linears."""
+    return max(attn_flops * cost_per_flop, kv_bytes * cost_per_byte) + linear_flops * cost_per_flop
+
+
+def step3_attention_cost_per_million_tokens(ctx, cost_per_flop, cost_per_byte, layers=61, n_q_heads=64, head_dim=256,
+                                            d_model=7168, q_rank=2048, kv_bytes_per_elem=1):
+    """The Step-3 row of the paper's decoding-cost table, from the model shape (8-bit cache)."""
+    per_token = attention_cost_per_token(
+        attn_flops_per_decoded_token(layers, n_q_heads, head_dim, ctx),
+        kv_bytes_per_decoded_token(layers, head_dim, kv_bytes_per_elem, ctx),
+        attn_linear_flops_per_decoded_token(layers, d_model, q_rank, n_q_heads, head_dim),
+        cost_per_flop, cost_per_byte)
+    return 1e6 * per_token
+

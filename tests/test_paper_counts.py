@@ -45,3 +45,31 @@ def test_wrong_shapes_miss_the_printed_figures():
     assert not _matches_printed(pc.kv_bytes_per_decoded_token(L, 128, 1, 8192), g["kv_bytes_per_token_8k"])
     assert not _matches_printed(pc.attn_flops_per_decoded_token(L, 32, 256, 8192), g["attn_flops_per_token_8k"])
     assert pc.arithmetic_intensity(64, 256, 2) == 64     # bf16 cache halves the intensity
+
+
+def test_step3_row_of_the_decoding_cost_table():
+    """Section 4.2: max(core flop cost, cache byte cost) + linear flop cost, per 1M tokens, on the four
+    accelerators of the unit-cost table; the printed Step-3 row has three decimals."""
+    g = _golden()
+    for ctx, tag in ((8192, "8k"), (32768, "32k")):
+        for hw in ("H800", "H20", "A800", "910B"):
+            cost = pc.step3_attention_cost_per_million_tokens(ctx, g["unit_cost_flop_" + hw], g["unit_cost_byte_" + hw])
+            printed = g[f"attn_cost_{tag}_{hw}"]
+            # half a unit of the last printed decimal, plus the rounding of the unit costs to three digits
+            assert abs(cost - printed) <= 0.0005 + 0.004 * printed, (ctx, hw, cost)
+
+
+def test_cost_formula_takes_the_larger_of_compute_and_memory():
+    # memory-bound on H800 (cheap flops), compute-bound on H20 (cheap bytes) at 8K: Section 4.2's point
+    g = _golden()
+    L, H, D = int(g["layers"]), int(g["n_q_heads"]), int(g["head_dim"])
+    fl, by = pc.attn_flops_per_decoded_token(L, H, D, 8192), pc.kv_bytes_per_decoded_token(L, D, 1, 8192)
+    assert fl * g["unit_cost_flop_H800"] < by * g["unit_cost_byte_H800"]
+    assert fl * g["unit_cost_flop_H20"] > by * g["unit_cost_byte_H20"]
+    assert pc.attention_cost_per_token(fl, by, 0.0, 1.0, 0.0) == fl and pc.attention_cost_per_token(fl, by, 0.0, 0.0, 1.0) == by
+    # a sum instead of a max, or a dropped linear term, misses the printed value
+    bad_sum = 1e6 * (fl * g["unit_cost_flop_H20"] + by * g["unit_cost_byte_H20"]
+                     + pc.attn_linear_flops_per_decoded_token(L, 7168, 2048, H, D) * g["unit_cost_flop_H20"])
+    assert abs(bad_sum - g["attn_cost_8k_H20"]) > 0.005
+    cf, cb = pc.unit_costs(3600.0, 1e15, 1e12)
+    assert cf == 1e-15 and cb == 1e-12
