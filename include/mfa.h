@@ -223,6 +223,28 @@ MFA_API mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_
                                   void* dst, int64_t dst_seq_stride_tokens, void* hip_stream);
 
 /*
+ * Several query tokens per sequence (Section 5.2 names multi-token prediction as the way to
+ * raise the arithmetic intensity of decoding attention: the new tokens share one pass over the
+ * cache).  The q_len new tokens are the last q_len rows of the cache (seq_lens[b] counts them);
+ * query token j of sequence b attends to the first seq_lens[b] - (q_len - 1 - j) cached tokens,
+ * i.e. causally among the new tokens.  A query token left without any token to attend to
+ * (seq_lens[b] < q_len) gets the zero row.
+ *   q    bf16 [B, q_len, n_q_heads, head_dim]
+ *   out  fp32 [B, q_len, n_q_heads, head_dim]     (written)
+ * q_len = 1 is mfa_decode_attn[_paged]; q_len = 2 is built (balanced work distribution only, i.e.
+ * B <= 4096); larger q_len returns MFA_ERR_UNSUPPORTED.  Everything else as for q_len = 1.
+ */
+MFA_API mfa_status mfa_decode_attn_multi(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                                 const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
+                                 int64_t kv_seq_stride_tokens, const int32_t* seq_lens, int32_t max_seq_len_hint,
+                                 int32_t B, int32_t q_len, float* out, void* hip_stream);
+MFA_API mfa_status mfa_decode_attn_paged_multi(mfa_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                                       const float* k_scale_pool, const float* v_scale_pool, mfa_kv_dtype kv_dtype,
+                                       int32_t n_pages, const int32_t* block_table, int32_t max_blocks_per_seq,
+                                       const int32_t* seq_lens, int32_t max_seq_len_hint, int32_t B, int32_t q_len,
+                                       float* out, void* hip_stream);
+
+/*
  * Measurement aid, not part of the serving path: while both handles are non-NULL
  * (hipEvent_t passed as void*, created by the caller with timing enabled), every
  * mfa_decode_attn / mfa_decode_attn_paged call on this context attaches the two

@@ -27,6 +27,7 @@ EXPORTS = [
     "mfa_query_proj", "mfa_decode_attn", "mfa_decode_attn_paged", "mfa_debug_gather_paged",
     "mfa_decode_num_splits", "mfa_debug_set_kernel_events", "mfa_debug_stream_read",
     "mfa_kv_append", "mfa_kv_append_paged", "mfa_debug_kv_record", "mfa_out_proj",
+    "mfa_decode_attn_multi", "mfa_decode_attn_paged_multi",
 ]
 
 
@@ -89,6 +90,11 @@ def lib():
     L.mfa_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i64, vp, i32, i32, vp, vp]
     L.mfa_decode_attn_paged.restype = ctypes.c_int
     L.mfa_decode_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, i32, vp, i32, i32, vp, vp]
+    L.mfa_decode_attn_multi.restype = ctypes.c_int
+    L.mfa_decode_attn_multi.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i64, vp, i32, i32, i32, vp, vp]
+    L.mfa_decode_attn_paged_multi.restype = ctypes.c_int
+    L.mfa_decode_attn_paged_multi.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, i32, vp, i32, i32, i32,
+                                              vp, vp]
     L.mfa_debug_gather_paged.restype = ctypes.c_int
     L.mfa_debug_gather_paged.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, i64, vp]
     L.mfa_debug_set_kernel_events.restype = ctypes.c_int
@@ -263,6 +269,75 @@ def mfa_decode_attn_paged(ctx: MfaContext, q, k_pool, v_pool, block_table, seq_l
                                        _ptr(v_scale_pool), kvd, n_pages, _ptr(block_table), block_table.shape[1],
                                        _ptr(seq_lens), int(max_seq_len_hint), B, _ptr(out), _stream()),
            "mfa_decode_attn_paged")
+    return out
+
+
+def mfa_decode_attn_multi(ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_hint, k_scale=None,
+                          v_scale=None, out=None):
+    """q bf16 [B,q_len,H,D]; caches as for mfa_decode_attn; out fp32 [B,q_len,H,D]."""
+    cfg = ctx.cfg
+    _want(q, torch.bfloat16, "q")
+    _want(seq_lens, torch.int32, "seq_lens")
+    if q.dim() != 4:
+        raise ValueError("q must be [B, q_len, H, D]")
+    B, q_len = q.shape[0], q.shape[1]
+    kvd = _kv_dtype(k_cache)
+    if v_cache.dtype != k_cache.dtype or not k_cache.is_contiguous() or not v_cache.is_contiguous():
+        raise TypeError("k_cache / v_cache must be contiguous and of one dtype")
+    S = k_cache.shape[1]
+    if tuple(q.shape) != (B, q_len, cfg.n_q_heads, cfg.head_dim) or tuple(k_cache.shape) != (B, S, cfg.head_dim) or \
+            tuple(v_cache.shape) != (B, S, cfg.head_dim) or tuple(seq_lens.shape) != (B,):
+        raise ValueError("attention shapes do not match")
+    for t, nm in ((k_scale, "k_scale"), (v_scale, "v_scale")):
+        if t is not None:
+            _want(t, torch.float32, nm)
+            if tuple(t.shape) != (B, S):
+                raise ValueError(nm + " shape")
+    if out is None:
+        out = torch.empty(B, q_len, cfg.n_q_heads, cfg.head_dim, dtype=torch.float32, device=q.device)
+    else:
+        _want(out, torch.float32, "out")
+        if tuple(out.shape) != tuple(q.shape):
+            raise ValueError("out shape")
+    _check(lib().mfa_decode_attn_multi(ctx.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale),
+                                       _ptr(v_scale), kvd, S, _ptr(seq_lens), int(max_seq_len_hint), B, q_len,
+                                       _ptr(out), _stream()), "mfa_decode_attn_multi")
+    return out
+
+
+def mfa_decode_attn_paged_multi(ctx: MfaContext, q, k_pool, v_pool, block_table, seq_lens, max_seq_len_hint,
+                                k_scale_pool=None, v_scale_pool=None, out=None):
+    """q bf16 [B,q_len,H,D]; pools and table as for mfa_decode_attn_paged; out fp32 [B,q_len,H,D]."""
+    cfg = ctx.cfg
+    _want(q, torch.bfloat16, "q")
+    _want(seq_lens, torch.int32, "seq_lens")
+    _want(block_table, torch.int32, "block_table")
+    if q.dim() != 4:
+        raise ValueError("q must be [B, q_len, H, D]")
+    B, q_len = q.shape[0], q.shape[1]
+    kvd = _kv_dtype(k_pool)
+    if v_pool.dtype != k_pool.dtype or not k_pool.is_contiguous() or not v_pool.is_contiguous():
+        raise TypeError("k_pool / v_pool must be contiguous and of one dtype")
+    n_pages = k_pool.shape[0]
+    if tuple(k_pool.shape) != (n_pages, cfg.page_size, cfg.head_dim) or tuple(v_pool.shape) != tuple(k_pool.shape) \
+            or block_table.shape[0] != B or tuple(seq_lens.shape) != (B,) or \
+            tuple(q.shape) != (B, q_len, cfg.n_q_heads, cfg.head_dim):
+        raise ValueError("paged attention shapes do not match")
+    for t, nm in ((k_scale_pool, "k_scale_pool"), (v_scale_pool, "v_scale_pool")):
+        if t is not None:
+            _want(t, torch.float32, nm)
+            if tuple(t.shape) != (n_pages, cfg.page_size):
+                raise ValueError(nm + " shape")
+    if out is None:
+        out = torch.empty(B, q_len, cfg.n_q_heads, cfg.head_dim, dtype=torch.float32, device=q.device)
+    else:
+        _want(out, torch.float32, "out")
+        if tuple(out.shape) != tuple(q.shape):
+            raise ValueError("out shape")
+    _check(lib().mfa_decode_attn_paged_multi(ctx.handle, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale_pool),
+                                             _ptr(v_scale_pool), kvd, n_pages, _ptr(block_table),
+                                             block_table.shape[1], _ptr(seq_lens), int(max_seq_len_hint), B, q_len,
+                                             _ptr(out), _stream()), "mfa_decode_attn_paged_multi")
     return out
 
 

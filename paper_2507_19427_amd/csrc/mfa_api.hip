@@ -86,8 +86,9 @@ Carve carve(const mfa_config* c, int32_t target)
     w.qproj = plan_qproj(c->d_model, c->q_rank);
     w.rows_pad = (c->max_batch + kQProjRows - 1) / kQProjRows * kQProjRows;
     size_t off = 0;
-    w.acc = off; off = align_up(off + w.max_items * kPartialAccFloats * sizeof(float), 256);
-    w.ml = off;  off = align_up(off + w.max_items * kPartialMlFloats * sizeof(float), 256);
+    // partial results: one slot per (workgroup segment, query token), up to two query tokens
+    w.acc = off; off = align_up(off + 2 * w.max_items * kPartialAccFloats * sizeof(float), 256);
+    w.ml = off;  off = align_up(off + 2 * w.max_items * kPartialMlFloats * sizeof(float), 256);
     w.seg = off; off = align_up(off + (size_t)c->max_batch * 2 * sizeof(int32_t), 256);
     // split-K partials of whichever product is running, and the bf16 k-step-major activations of the
     // second query product / the output projection
@@ -133,6 +134,7 @@ void fill_common(const mfa_ctx* ctx, AttnArgs& a, int32_t B, int32_t hint)
     a.n_splits = p.n_splits;
     a.chunk_tokens = p.chunk_tokens;
     a.B = B;
+    a.q_len = 1;
     a.max_seq_len_hint = hint;
     a.ws_acc = ctx->ws_acc;
     a.ws_ml = ctx->ws_ml;
@@ -339,20 +341,56 @@ mfa_status mfa_out_proj(mfa_ctx* ctx, const float* attn_out, const void* w_o, vo
     return launch_out_proj(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }
 
-mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
-                           const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
-                           int64_t kv_seq_stride_tokens, const int32_t* seq_lens, int32_t max_seq_len_hint,
-                           int32_t B, float* out, void* hip_stream)
+mfa_status mfa_decode_attn_multi(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                                 const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
+                                 int64_t kv_seq_stride_tokens, const int32_t* seq_lens, int32_t max_seq_len_hint,
+                                 int32_t B, int32_t q_len, float* out, void* hip_stream)
 {
     const mfa_status st = check_attn_common(ctx, q, k_cache, v_cache, k_scale, v_scale, kv_dtype, seq_lens,
                                             max_seq_len_hint, B, out);
     if (st != MFA_OK) return st;
     if (kv_seq_stride_tokens < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
+    if (q_len < 1) return MFA_ERR_INVALID_ARG;
+    if (q_len > 2) return MFA_ERR_UNSUPPORTED;
     AttnArgs a{};
     a.q = q; a.k = k_cache; a.v = v_cache; a.k_scale = k_scale; a.v_scale = v_scale;
     a.seq_lens = seq_lens; a.block_table = nullptr; a.out = out;
     a.seq_stride_tokens = kv_seq_stride_tokens; a.max_blocks_per_seq = 0;
     fill_common(ctx, a, B, max_seq_len_hint);
+    a.q_len = q_len;
+    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream), ctx->ev_before, ctx->ev_after);
+    if (e == hipErrorNotSupported) return MFA_ERR_UNSUPPORTED;
+    return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+}
+
+mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                           const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
+                           int64_t kv_seq_stride_tokens, const int32_t* seq_lens, int32_t max_seq_len_hint,
+                           int32_t B, float* out, void* hip_stream)
+{
+    return mfa_decode_attn_multi(ctx, q, k_cache, v_cache, k_scale, v_scale, kv_dtype, kv_seq_stride_tokens, seq_lens,
+                                 max_seq_len_hint, B, 1, out, hip_stream);
+}
+
+mfa_status mfa_decode_attn_paged_multi(mfa_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                                       const float* k_scale_pool, const float* v_scale_pool, mfa_kv_dtype kv_dtype,
+                                       int32_t n_pages, const int32_t* block_table, int32_t max_blocks_per_seq,
+                                       const int32_t* seq_lens, int32_t max_seq_len_hint, int32_t B, int32_t q_len,
+                                       float* out, void* hip_stream)
+{
+    const mfa_status st = check_attn_common(ctx, q, k_pool, v_pool, k_scale_pool, v_scale_pool, kv_dtype, seq_lens,
+                                            max_seq_len_hint, B, out);
+    if (st != MFA_OK) return st;
+    if (!block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u) || n_pages < 1) return MFA_ERR_INVALID_ARG;
+    if ((int64_t)max_blocks_per_seq * kPage < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
+    if (q_len < 1) return MFA_ERR_INVALID_ARG;
+    if (q_len > 2) return MFA_ERR_UNSUPPORTED;
+    AttnArgs a{};
+    a.q = q; a.k = k_pool; a.v = v_pool; a.k_scale = k_scale_pool; a.v_scale = v_scale_pool;
+    a.seq_lens = seq_lens; a.block_table = block_table; a.out = out;
+    a.seq_stride_tokens = 0; a.max_blocks_per_seq = max_blocks_per_seq;
+    fill_common(ctx, a, B, max_seq_len_hint);
+    a.q_len = q_len;
     const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream), ctx->ev_before, ctx->ev_after);
     if (e == hipErrorNotSupported) return MFA_ERR_UNSUPPORTED;
     return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
@@ -364,19 +402,8 @@ mfa_status mfa_decode_attn_paged(mfa_ctx* ctx, const void* q, const void* k_pool
                                  const int32_t* seq_lens, int32_t max_seq_len_hint, int32_t B, float* out,
                                  void* hip_stream)
 {
-    const mfa_status st = check_attn_common(ctx, q, k_pool, v_pool, k_scale_pool, v_scale_pool, kv_dtype, seq_lens,
-                                            max_seq_len_hint, B, out);
-    if (st != MFA_OK) return st;
-    if (!block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u) || n_pages < 1) return MFA_ERR_INVALID_ARG;
-    if ((int64_t)max_blocks_per_seq * kPage < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
-    AttnArgs a{};
-    a.q = q; a.k = k_pool; a.v = v_pool; a.k_scale = k_scale_pool; a.v_scale = v_scale_pool;
-    a.seq_lens = seq_lens; a.block_table = block_table; a.out = out;
-    a.seq_stride_tokens = 0; a.max_blocks_per_seq = max_blocks_per_seq;
-    fill_common(ctx, a, B, max_seq_len_hint);
-    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream), ctx->ev_before, ctx->ev_after);
-    if (e == hipErrorNotSupported) return MFA_ERR_UNSUPPORTED;
-    return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
+    return mfa_decode_attn_paged_multi(ctx, q, k_pool, v_pool, k_scale_pool, v_scale_pool, kv_dtype, n_pages, block_table,
+                                       max_blocks_per_seq, seq_lens, max_seq_len_hint, B, 1, out, hip_stream);
 }
 
 mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_t row_bytes, int32_t n_pages,

@@ -48,7 +48,10 @@ __device__ __forceinline__ int64_t tile_row0(const AttnArgs& a, int b, int tile_
     return PAGED ? (int64_t)page * kPage : (int64_t)b * a.seq_stride_tokens + tile_t0;
 }
 
-template <bool PAGED>
+// QL = query tokens per sequence.  1: wave = 4*(token half of the tile) + head group.  2: wave =
+// 4*(query token) + head group, and every wave works through both halves of each tile; query token j
+// attends to the first len - (QL - 1 - j) cached tokens (the new tokens are the last QL of the cache).
+template <bool PAGED, int QL>
 __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -70,7 +73,8 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
         first_segment = false;
 
         QFrags<false> q;
-        load_q_fragments(q.f, a.q, r.b, 16 * wq + n, g);
+        load_q_fragments(q.f, a.q, QL == 2 ? 2 * r.b + grp : r.b, 16 * wq + n, g);
+        const int t1_mine = QL == 2 ? (r.t1 < r.len - 1 + grp ? r.t1 : r.len - 1 + grp) : r.t1;   // grp = query token when QL == 2
 
         // Wave w brings rows [8w, 8w+8) of the tile's K and V: all in unit w/4.  Rows at or past t1
         // re-read the last valid token, so nothing outside the sequence is touched and every LDS row
@@ -110,11 +114,21 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
                 issue_tile(it + 1, slot ^ 1, page_next);
                 if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
             }
-            const int unit = slot * kSlotBytes + grp * kUnitBytes;
-            process_unit<false>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + grp * kUnitTokens,
-                                r.t1, a.scale_log2e, n, g, 0, 0);
+            if (QL == 2) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int unit = slot * kSlotBytes + u * kUnitBytes;
+                    process_unit<false>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + u * kUnitTokens,
+                                        t1_mine, a.scale_log2e, n, g, 0, 0);
+                }
+            } else {
+                const int unit = slot * kSlotBytes + grp * kUnitBytes;
+                process_unit<false>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + grp * kUnitTokens,
+                                    t1_mine, a.scale_log2e, n, g, 0, 0);
+            }
         }
-        finish_segment(st, lds_base, a, r, wq, grp, lane);
+        if (QL == 2) finish_segment_two(st, a, r, grp, wq, lane);
+        else         finish_segment(st, lds_base, a, r, wq, grp, lane);
     }
 }
 
@@ -168,7 +182,7 @@ __device__ __forceinline__ void drain_tiles(Fp8TileRegs& t, Fp8TileRegs& u)
                  :: "memory");
 }
 
-template <bool PAGED>
+template <bool PAGED, int QL>
 __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -262,7 +276,8 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
         // The query fragments are loaded by ordinary loads: the compiler completes them, and with them
         // everything above, right here instead of inside the loop.
         QFrags<true> q;
-        load_split_q_fp8(q, a.q, r.b, 16 * wq + n, g);
+        load_split_q_fp8(q, a.q, QL == 2 ? 2 * r.b + grp : r.b, 16 * wq + n, g);
+        const int t1_mine = QL == 2 ? (r.t1 < r.len - 1 + grp ? r.t1 : r.len - 1 + grp) : r.t1;   // grp = query token when QL == 2
         asm volatile("" : "+v"(q.hi[0]), "+v"(q.hi[1]), "+v"(q.lo[0]), "+v"(q.lo[1]));
         drain_tiles(regs[0], regs[1]);
         store_tile(regs[0], 0);
@@ -277,10 +292,14 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
             store_tile(regs[P ^ 1], P ^ 1);                                 // values of tile t+1
             load_tile(regs[P ^ 1], t + 3);
             issue_keys(t + 2, kslot == 0 ? 2 : kslot - 1);                  // (t + 2) % 3, the slot tile t-1 has left
-            const int scales = kFp8ScaleBase + P * 512 + grp * kUnitTokens * 4;
-            process_unit<true>(st, q, lds_base, kFp8KBase + kslot * kFp8KSlotBytes + grp * kUnitTokens * 256,
-                               P * kFp8VImageBytes + grp * 16384, r.t0 + t * kTile + grp * kUnitTokens, r.t1,
-                               a.scale_log2e, n, g, scales, scales + 256);
+            auto unit = [&](int u) {
+                const int scales = kFp8ScaleBase + P * 512 + u * kUnitTokens * 4;
+                process_unit<true>(st, q, lds_base, kFp8KBase + kslot * kFp8KSlotBytes + u * kUnitTokens * 256,
+                                   P * kFp8VImageBytes + u * 16384, r.t0 + t * kTile + u * kUnitTokens, t1_mine,
+                                   a.scale_log2e, n, g, scales, scales + 256);
+            };
+            if (QL == 2) { unit(0); unit(1); }
+            else         unit(grp);
             kslot = kslot == 2 ? 0 : kslot + 1;
         };
         for (int t = 0; t < r.n_tiles; t += 2) {
@@ -289,7 +308,8 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
             step(std::integral_constant<int, 1>{}, t + 1);
         }
         drain_tiles(regs[0], regs[1]);        // the repeats of the last tile issued past the end
-        finish_segment(st, lds_base, a, r, wq, grp, lane);
+        if (QL == 2) finish_segment_two(st, a, r, grp, wq, lane);
+        else         finish_segment(st, lds_base, a, r, wq, grp, lane);
     }
 }
 
@@ -300,10 +320,12 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
 // taken four at a time so that their loads are independent and in flight together.
 __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B * 4096 float4
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B * q_len * 4096 float4
     const int p = (int)(idx & 4095);                                  // position in the partial's lane-order layout
-    const int b = (int)(idx >> 12);
-    if (b >= a.B) return;
+    const int bq = (int)(idx >> 12);                                  // sequence * q_len + query token
+    if (bq >= a.B * a.q_len) return;
+    const int b = bq / a.q_len;
+    const int qtok = bq - b * a.q_len;
     const int lane = p & 63;
     const int db = (p >> 6) & 15;
     const int wq = p >> 10;
@@ -311,7 +333,8 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
     const int d = 16 * db + 4 * (lane >> 4);
     int L = a.seq_lens[b];
     L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
-    float4* const o = (float4*)(a.out + ((size_t)b * kHeads + h) * kHeadDim + d);
+    float4* const o = (float4*)(a.out + ((size_t)bq * kHeads + h) * kHeadDim + d);
+    const int L_mine = L - (a.q_len - 1 - qtok);                      // tokens this query token attends to
     int n_valid;
     size_t item0;
     if (a.n_wgs > 0) {                                                // balanced schedule
@@ -324,8 +347,11 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
         n_valid = (L + a.chunk_tokens - 1) / a.chunk_tokens;          // <= n_splits
         item0 = (size_t)b * a.n_splits;
     }
-    const float2* ml_base = (const float2*)a.ws_ml + item0 * kHeads + h;
-    const float4* acc_base = (const float4*)a.ws_acc + item0 * (kHeads * kHeadDim / 4) + p;
+    if (L_mine <= 0) { *o = make_float4(0.f, 0.f, 0.f, 0.f); return; }   // (only with two query tokens and L = 1)
+    const size_t slot0 = item0 * a.q_len + qtok;                      // partial of (item, query token) at item*q_len + qtok
+    const size_t slot_step = (size_t)a.q_len;
+    const float2* ml_base = (const float2*)a.ws_ml + slot0 * kHeads + h;
+    const float4* acc_base = (const float4*)a.ws_acc + slot0 * (kHeads * kHeadDim / 4) + p;
 
     float m = -INFINITY;
     for (int s0 = 0; s0 < n_valid; s0 += 4) {
@@ -333,7 +359,7 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u < n_valid ? s0 + u : n_valid - 1;
-            mm[u] = ml_base[(size_t)s * kHeads].x;
+            mm[u] = ml_base[(size_t)s * slot_step * kHeads].x;
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) m = fmaxf(m, mm[u]);
@@ -346,12 +372,12 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u < n_valid ? s0 + u : n_valid - 1;
-            ml[u] = ml_base[(size_t)s * kHeads];
-            v[u] = acc_base[(size_t)s * (kHeads * kHeadDim / 4)];
+            ml[u] = ml_base[(size_t)s * slot_step * kHeads];
+            v[u] = acc_base[(size_t)s * slot_step * (kHeads * kHeadDim / 4)];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float w = s0 + u < n_valid ? fast_exp2(ml[u].x - m) : 0.f;
+            const float w = s0 + u < n_valid ? fast_exp2(ml[u].x - m) : 0.f;     // a piece without tokens has m = -inf: weight 0
             sum.x += w * v[u].x; sum.y += w * v[u].y; sum.z += w * v[u].z; sum.w += w * v[u].w;
             l += w * ml[u].y;
         }
@@ -424,17 +450,28 @@ int32_t balanced_workgroups(int32_t B, int32_t max_seq_len_hint, int32_t target_
     return (int32_t)(max_tiles < target_items ? max_tiles : target_items);
 }
 
+namespace {
+
+template <int QL>
+const void* attn_kernel(mfa_kv_dtype kv_dtype, bool paged)
+{
+    if (kv_dtype == MFA_KV_BF16) return paged ? (const void*)decode_bf16_kernel<true, QL> : (const void*)decode_bf16_kernel<false, QL>;
+    return paged ? (const void*)decode_fp8_kernel<true, QL> : (const void*)decode_fp8_kernel<false, QL>;
+}
+
+}  // namespace
+
 hipError_t prepare_decode_attn_kernels()
 {
-    hipError_t e;
-    e = hipFuncSetAttribute((const void*)decode_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)decode_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)decode_fp8_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)decode_fp8_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
-    return e;
+    for (int dt = 0; dt < 2; ++dt)
+        for (int paged = 0; paged < 2; ++paged) {
+            const mfa_kv_dtype kvd = dt ? MFA_KV_FP8_E4M3 : MFA_KV_BF16;
+            hipError_t e = hipFuncSetAttribute(attn_kernel<1>(kvd, paged != 0), hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(attn_kernel<2>(kvd, paged != 0), hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
+            if (e != hipSuccess) return e;
+        }
+    return hipSuccess;
 }
 
 hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream,
@@ -443,21 +480,20 @@ hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStrea
     const dim3 grid((unsigned)(a.n_wgs > 0 ? a.n_wgs : a.B * a.n_splits));
     const dim3 block(kAttnThreads);
     if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return hipErrorNotSupported;
+    if (a.q_len != 1 && !(a.q_len == 2 && a.n_wgs > 0)) return hipErrorNotSupported;   // two query tokens: balanced schedule only
     // The two events, when given, are attached to the streaming kernel's own dispatch: they take the
     // times at which that kernel starts and ends on the device, with no launch gap inside the interval.
     if (!(ev_before && ev_after)) ev_before = ev_after = nullptr;
-    const unsigned kAttnLdsTotal_ = a.n_wgs > 0 ? kAttnLdsTotal : kSchedLdsOffset;   // the schedule's arrays only if used
-    if (kv_dtype == MFA_KV_BF16) {
-        if (a.block_table) hipExtLaunchKernelGGL(decode_bf16_kernel<true>, grid, block, kAttnLdsTotal_, stream, ev_before, ev_after, 0, a);
-        else               hipExtLaunchKernelGGL(decode_bf16_kernel<false>, grid, block, kAttnLdsTotal_, stream, ev_before, ev_after, 0, a);
-    } else {
-        if (a.block_table) hipExtLaunchKernelGGL(decode_fp8_kernel<true>, grid, block, kAttnLdsTotal_, stream, ev_before, ev_after, 0, a);
-        else               hipExtLaunchKernelGGL(decode_fp8_kernel<false>, grid, block, kAttnLdsTotal_, stream, ev_before, ev_after, 0, a);
-    }
-    hipError_t e = hipGetLastError();
+    const unsigned lds_bytes = a.n_wgs > 0 ? kAttnLdsTotal : kSchedLdsOffset;   // the schedule's arrays only if used
+    const void* kernel = a.q_len == 2 ? attn_kernel<2>(kv_dtype, a.block_table != nullptr) : attn_kernel<1>(kv_dtype, a.block_table != nullptr);
+    AttnArgs args = a;
+    void* params[] = {&args};
+    hipError_t e = hipExtLaunchKernel(kernel, grid, block, params, lds_bytes, stream, ev_before, ev_after, 0);
+    if (e != hipSuccess) return e;
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (a.n_wgs > 0 || a.n_splits > 1) {
-        const unsigned blocks = (unsigned)(((size_t)a.B * kHeads * (kHeadDim / 4) + 255) / 256);
+        const unsigned blocks = (unsigned)(((size_t)a.B * a.q_len * kHeads * (kHeadDim / 4) + 255) / 256);
         hipLaunchKernelGGL(merge_splits_kernel, dim3(blocks), dim3(256), 0, stream, a);
         e = hipGetLastError();
     }

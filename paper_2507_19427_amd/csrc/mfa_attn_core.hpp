@@ -314,6 +314,7 @@ __device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, c
 // ragged).  Its result is the sequence's final output (final_result) or a partial in `slot`.
 struct Segment {
     int b, t0, t1, n_tiles, slot;
+    int len;              // the sequence's (clamped) length
     bool final_result;
 };
 
@@ -325,6 +326,7 @@ __device__ __forceinline__ void make_uniform(Segment& r)
     r.t1 = __builtin_amdgcn_readfirstlane(r.t1);
     r.n_tiles = __builtin_amdgcn_readfirstlane(r.n_tiles);
     r.slot = __builtin_amdgcn_readfirstlane(r.slot);
+    r.len = __builtin_amdgcn_readfirstlane(r.len);
     r.final_result = __builtin_amdgcn_readfirstlane((int)r.final_result) != 0;
 }
 
@@ -335,6 +337,31 @@ __device__ __forceinline__ void finish_segment(WaveState& st, lds_ptr_t lds_base
     __syncthreads();                                  // every wave is done reading the tile buffers
     if (grp == 0) finish_half<0, 8>(st, lds_base, a, r.b, r.slot, r.final_result, wq, grp, lane);
     else          finish_half<8, 0>(st, lds_base, a, r.b, r.slot, r.final_result, wq, grp, lane);
+}
+
+// Two query tokens per sequence (the wave layout is then 2 query tokens x 4 head groups, and every wave
+// has seen all tokens of the segment): no exchange, each wave stores its 16 rows.  The partial of a
+// (segment, query token) sits at slot*2 + query token in the same lane-order layout.  A query token
+// that saw no cached token in this segment leaves m = -inf, l = 0 and a zero accumulator; as a final
+// result that is the zero row.
+__device__ __forceinline__ void finish_segment_two(WaveState& st, const AttnArgs& a, const Segment& r, int qtok, int wq, int lane)
+{
+    const int n = lane & 15, g = lane >> 4;
+    const int head = 16 * wq + n;
+    const float l = head_sum(st.l);
+    const size_t row = (size_t)r.b * 2 + qtok;
+    if (r.final_result) {
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
+        float* o = a.out + (row * kHeads + head) * kHeadDim + 4 * g;
+#pragma unroll
+        for (int db = 0; db < 16; ++db) *(f32x4*)(o + 16 * db) = st.acc[db] * inv;
+    } else {
+        const size_t slot = (size_t)r.slot * 2 + qtok;
+        f32x4* part = (f32x4*)a.ws_acc + slot * (kHeads * kHeadDim / 4) + (size_t)wq * 16 * 64 + lane;
+#pragma unroll
+        for (int db = 0; db < 16; ++db) part[db * 64] = st.acc[db];
+        if (g == 0) *(float2*)(a.ws_ml + (slot * kHeads + head) * 2) = make_float2(st.m, l);
+    }
 }
 
 __device__ __forceinline__ int clamped_len(const AttnArgs& a, int b)
@@ -524,6 +551,7 @@ __device__ __forceinline__ bool schedule_next(const AttnArgs& a, lds_ptr_t lds_b
         r.t0 = split * a.chunk_tokens;
         r.t1 = (r.t0 + a.chunk_tokens < L) ? r.t0 + a.chunk_tokens : L;
         r.n_tiles = (r.t1 - r.t0 + kTile - 1) / kTile;
+        r.len = L;
         r.slot = item;
         r.final_result = a.n_splits == 1;
         if (r.t0 >= r.t1) {
@@ -553,6 +581,7 @@ __device__ __forceinline__ bool schedule_next(const AttnArgs& a, lds_ptr_t lds_b
     r.t0 = (s.lo - seq0) * kTile;
     r.t1 = (end - seq0) * kTile < L ? (end - seq0) * kTile : L;
     r.n_tiles = end - s.lo;
+    r.len = L;
     r.final_result = seq0 >= s.my_lo && seq1 <= s.hi;                // the whole sequence lies in my range
     r.slot = (int)blockIdx.x + b;
     if (s.lo == seq0) {                                               // I hold its first tile: tell the merge

@@ -38,20 +38,21 @@ constexpr size_t kPartialAccFloats = (size_t)kHeads * kHeadDim;
 constexpr size_t kPartialMlFloats = (size_t)kHeads * 2;
 
 struct AttnArgs {
-    const void* q;                 // bf16 [B,64,256]
+    const void* q;                 // bf16 [B,q_len,64,256]
     const void* k;                 // cache or pool
     const void* v;
     const float* k_scale;          // fp8 only
     const float* v_scale;
     const int32_t* seq_lens;       // device
     const int32_t* block_table;    // device, NULL for contiguous
-    float* out;                    // fp32 [B,64,256]
+    float* out;                    // fp32 [B,q_len,64,256]
     float* ws_acc;                 // [B*n_splits][64][256]
     float* ws_ml;                  // [B*n_splits][64][2]
     int32_t* ws_seg;               // balanced schedule: per sequence (first partial slot, number of partials)
     int64_t seq_stride_tokens;     // contiguous only
     int32_t max_blocks_per_seq;    // paged only
     int32_t B;
+    int32_t q_len;                 // query tokens per sequence: 1, or 2 (q, out, partial slots are then [.., 2, ..])
     int32_t n_wgs;                 // > 0: balanced schedule over this many workgroups; 0: fixed splits below
     int32_t n_splits;
     int32_t chunk_tokens;

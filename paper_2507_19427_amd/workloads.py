@@ -122,6 +122,15 @@ def make_contiguous_case(name, seed, B, S, seq_lens=None, kv_dtype="bf16", poiso
     return case
 
 
+def make_multi_query(case: AttnCase, q_len, seed):
+    """bf16 [B, q_len, H, D] queries for a step that decodes q_len tokens per sequence (the same
+    distribution as the single query; the last of them is the case's own q)."""
+    gen = torch.Generator().manual_seed(seed)
+    B, H, D = case.q.shape
+    extra = _randn(gen, B, q_len - 1, H, D).to(torch.bfloat16)
+    return torch.cat([extra, case.q.unsqueeze(1)], dim=1).contiguous()
+
+
 def make_paged_case(name, seed, seq_lens, kv_dtype="bf16", poison=True, spare_pages=64,
                     max_blocks=None, page=PAGE_SIZE, H=N_Q_HEADS, D=HEAD_DIM,
                     scale=SOFTMAX_SCALE) -> AttnCase:

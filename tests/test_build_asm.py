@@ -92,9 +92,10 @@ def _check_pipeline(lines):
     assert partial_waits >= 2, "the two steps of the unrolled loop each wait with vmcnt(5)"
 
 
+@pytest.mark.parametrize("q_len", [1, 2])
 @pytest.mark.parametrize("paged", [0, 1])
-def test_fp8_pipeline_registers_stay_untouched_between_load_and_wait(asm_text, paged):
-    _check_pipeline(_kernel_body(asm_text, f"_ZN3mfa17decode_fp8_kernelILb{paged}EEEvNS_8AttnArgsE"))
+def test_fp8_pipeline_registers_stay_untouched_between_load_and_wait(asm_text, paged, q_len):
+    _check_pipeline(_kernel_body(asm_text, f"_ZN3mfa17decode_fp8_kernelILb{paged}ELi{q_len}EEEvNS_8AttnArgsE"))
 
 
 def _snippet(between):
