@@ -11,7 +11,8 @@ cache cannot serve it.
 
 --workload selects one of the other seeded workloads (ragged paged, long context, query path + fp8
 cache, the whole attention layer at the paper's 8K / 32K contexts); they exist so that kernel profiles of
-those shapes can be taken with this same program.
+those shapes can be taken with this same program; cfg2q2 / fp8q2 run the step with two query tokens per
+sequence.
 
 Prints ONE JSON line: metric/value = KV tokens per second, plus
   roofline      HBM roofline of the streaming attention kernel from HIP-event timings taken in the timed region
@@ -45,6 +46,7 @@ class Workload:
         self.T = 0                 # KV tokens per step
         self.kv_bytes_per_token = 0
         self.B = 0
+        self.q_len = 1
         self.extra_config = {}
         self.case = None           # host case for the oracle sample (contiguous bf16 only)
         self.keep = []
@@ -75,7 +77,7 @@ def build_workload(key, mfa, W, n_sets):
         w.desc = ("configs[%d]: B=%d, 64 q heads, 1 shared K/V head, head_dim 256, ctx %d, contiguous bf16 KV"
                   % (1 if key == "cfg2" else 3, B, S))
         w.metric = "KV tokens/s, MFA decode attention, B=%d, ctx %d, bf16, 1 GPU" % (B, S)
-        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<false>", 1024
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<false, 1>", 1024
         w.T, w.B, w.case = case.kv_tokens, B, case
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S)}
     elif key == "cfg3":
@@ -92,7 +94,7 @@ def build_workload(key, mfa, W, n_sets):
         w.desc = ("configs[2]: B=128, ctx uniform in [1024, 8192], 64-token pages behind a permuted block table, "
                   "bf16 KV")
         w.metric = "KV tokens/s, MFA decode attention, B=128, ragged paged ctx 1K-8K, bf16, 1 GPU"
-        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<true>", 1024
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<true, 1>", 1024
         w.T, w.B = case.kv_tokens, B
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S), "max_ctx": S}
     elif key == "cfg5":
@@ -118,10 +120,35 @@ def build_workload(key, mfa, W, n_sets):
         w.desc = ("configs[4]: B=128, query path 7168 -> 2048 -> RMSNorm -> 64x256, then attention over ctx 8192 of "
                   "fp8 e4m3 KV with per-token fp32 scales")
         w.metric = "KV tokens/s, MFA query path + decode attention, B=128, ctx 8192, fp8 KV, 1 GPU"
-        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16 (fp8 e4m3 KV storage)", "mfa::decode_fp8_kernel<false>", 520
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16 (fp8 e4m3 KV storage)", "mfa::decode_fp8_kernel<false, 1>", 520
         w.T, w.B = case.kv_tokens, B
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S)}
         w.keep = [x, w_qa, w_qb]
+    elif key in ("cfg2q2", "fp8q2"):
+        # Two new tokens per sequence in one pass over the cache (the multi-token step of Section 5.2):
+        # same cache shapes as configs[1] / the cache of configs[4], twice the arithmetic per byte.
+        fp8 = key == "fp8q2"
+        case = (W.make_contiguous_case(key, 6, B=128, S=8192, kv_dtype="fp8", poison=False) if fp8
+                else W.config2_step3(poison=False))
+        B, S = case.B, case.k.shape[1]
+        w.ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=S))
+        q, lens = W.make_multi_query(case, 2, 9).cuda(), case.seq_lens.cuda()
+        ks, vs = _roll_sets(case.k.cuda(), n_sets), _roll_sets(case.v.cuda(), n_sets)
+        kss = _roll_sets(case.k_scale.cuda(), n_sets) if fp8 else [None] * n_sets
+        vss = _roll_sets(case.v_scale.cuda(), n_sets) if fp8 else [None] * n_sets
+        out = torch.empty(B, 2, 64, 256, dtype=torch.float32, device="cuda")
+        w.steps = [mfa.PreparedDecodeAttn(w.ctx, q, ks[j], vs[j], lens, S, out, k_scale=kss[j], v_scale=vss[j])
+                   for j in range(n_sets)]
+        w.read_pairs = list(zip(ks, vs))
+        w.desc = ("two query tokens per sequence: B=%d, 64 q heads, 1 shared K/V head, head_dim 256, ctx %d, "
+                  "contiguous %s KV" % (B, S, "fp8 e4m3 (per-token fp32 scales)" if fp8 else "bf16"))
+        w.metric = "KV tokens/s, MFA decode attention with 2 query tokens, B=%d, ctx %d, %s, 1 GPU" % (
+            B, S, "fp8 KV" if fp8 else "bf16")
+        w.dtype = "bf16 (fp8 e4m3 KV storage)" if fp8 else "bf16"
+        w.kernel = "mfa::decode_fp8_kernel<false, 2>" if fp8 else "mfa::decode_bf16_kernel<false, 2>"
+        w.kv_bytes_per_token = 520 if fp8 else 1024
+        w.T, w.B, w.q_len = case.kv_tokens, B, 2
+        w.extra_config = {"query_tokens_per_sequence": 2}
     elif key in ("layer8k", "layer32k"):
         # One whole attention layer of a decode step, the unit of the paper's attention-latency table
         # (Section 7.3: 64 sequences per GPU, context 8K / 32K): query path, key/value projection of the
@@ -157,7 +184,7 @@ def build_workload(key, mfa, W, n_sets):
                   "7168 -> 2x256 + cache record, attention over ctx %d of contiguous bf16 KV, output projection "
                   "16384 -> 7168; all weights bf16" % S)
         w.metric = "KV tokens/s, MFA attention layer (linears + core attention), B=64, ctx %d, bf16, 1 GPU" % S
-        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<false>", 1024
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<false, 1>", 1024
         w.T, w.B = B * S, B
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S),
                           "weight_bytes_per_step": 2 * (qc.w_qa.numel() + qc.w_qb.numel() + w_kv.numel() + w_o.numel()),
@@ -175,7 +202,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "layer8k", "layer32k"), default="cfg2")
+    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "cfg2q2", "fp8q2", "layer8k", "layer32k"), default="cfg2")
     ap.add_argument("--buffer-sets", type=int, default=None, help="distinct KV buffer sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
@@ -231,7 +258,7 @@ def main():
         torch.cuda.synchronize()
 
     value = T / (ms_per_step * 1e-3)
-    algo_bytes = T * w.kv_bytes_per_token + w.B * (Q_BYTES_PER_SEQ + OUT_BYTES_PER_SEQ)
+    algo_bytes = T * w.kv_bytes_per_token + w.B * w.q_len * (Q_BYTES_PER_SEQ + OUT_BYTES_PER_SEQ)
     achieved = algo_bytes / (ev_mean * 1e-3) / 1e9
     roofline = {
         "bound": "hbm",

@@ -444,20 +444,24 @@ def mfa_out_proj(ctx: MfaContext, attn_out, w_o, y=None):
 
 
 class PreparedDecodeAttn:
-    """mfa_decode_attn with its arguments marshalled once: calling the object only crosses the C
-    boundary (for loops that must not pay Python-side checks per step).  The tensors are kept alive."""
+    """mfa_decode_attn (q [B,H,D]) or mfa_decode_attn_multi (q [B,q_len,H,D]) with its arguments marshalled
+    once: calling the object only crosses the C boundary (for loops that must not pay Python-side checks
+    per step).  The tensors are kept alive."""
 
     def __init__(self, ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_hint, out, k_scale=None,
                  v_scale=None):
-        mfa_decode_attn(ctx, q, k_cache, v_cache, seq_lens, max_seq_len_hint, k_scale=k_scale, v_scale=v_scale,
-                        out=out)                       # validates shapes and types once
+        multi = q.dim() == 4
+        check = mfa_decode_attn_multi if multi else mfa_decode_attn
+        check(ctx, q, k_cache, v_cache, seq_lens, max_seq_len_hint, k_scale=k_scale, v_scale=v_scale,
+              out=out)                                 # validates shapes and types once
         self._keep = (ctx, q, k_cache, v_cache, seq_lens, out, k_scale, v_scale)
-        self._fn = lib().mfa_decode_attn
-        self._args = (ctx.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
-                      _kv_dtype(k_cache), k_cache.shape[1], _ptr(seq_lens), int(max_seq_len_hint), q.shape[0],
-                      _ptr(out), _stream())
+        self._name = "mfa_decode_attn_multi" if multi else "mfa_decode_attn"
+        self._fn = getattr(lib(), self._name)
+        head = (ctx.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
+                _kv_dtype(k_cache), k_cache.shape[1], _ptr(seq_lens), int(max_seq_len_hint), q.shape[0])
+        self._args = head + ((q.shape[1],) if multi else ()) + (_ptr(out), _stream())
 
     def __call__(self):
         st = self._fn(*self._args)
         if st != MFA_OK:
-            raise MfaError(st, "mfa_decode_attn")
+            raise MfaError(st, self._name)
