@@ -215,39 +215,52 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<FP8>& q
         }
     }
 
-    // ---- online softmax in the log2 domain; tokens at or past t1 are masked
+    // ---- online softmax in the log2 domain.  The raw scores are compared first and scaled inside the
+    // exponent's fused multiply-add (the scale is positive); only a unit that reaches past t1, the last
+    // of a sequence at most, spends instructions on masking.
     float sv[8];
-    float m_new = st.m;
+    float m_raw = -INFINITY;
+    if (unit_t0 + kUnitTokens <= t1) {
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
+        for (int j = 0; j < 8; ++j) {
+            sv[j] = s[j >> 2][j & 3];
+            m_raw = fmaxf(m_raw, sv[j]);
+        }
+    } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int tok = unit_t0 + 16 * tb + 4 * g + i;
-            float x = s[tb][i] * scale_log2e;
-            x = tok < t1 ? x : -INFINITY;
-            sv[4 * tb + i] = x;
-            m_new = fmaxf(m_new, x);
+        for (int j = 0; j < 8; ++j) {
+            const int tok = unit_t0 + 16 * (j >> 2) + 4 * g + (j & 3);
+            sv[j] = tok < t1 ? s[j >> 2][j & 3] : -INFINITY;
+            m_raw = fmaxf(m_raw, sv[j]);
         }
     }
-    m_new = head_max(m_new);
+    const float m_new = head_max(fmaxf(st.m, m_raw * scale_log2e));
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = fast_exp2(st.m - m_safe);      // 0 while nothing has been accumulated
     st.m = m_new;
 
     bf16x8 pf;
     float psum = 0.f;
+    if (FP8) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const float p = fast_exp2(sv[j] - m_safe);
-        if (FP8) {
+        for (int j = 0; j < 8; ++j) {
             // the value scale rides on the weight; the normaliser sums the unscaled weight
+            const float p = fast_exp2(__builtin_fmaf(sv[j], scale_log2e, -m_safe));
             pf[j] = (__bf16)(p * vsc[j >> 2][j & 3]);
             psum += p;
-        } else {
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; j += 2) {
             // normalise by the sum of the rounded weights actually multiplied into V
-            const __bf16 pb = (__bf16)p;
-            pf[j] = pb;
-            psum += (float)pb;
+            const float p0 = fast_exp2(__builtin_fmaf(sv[j], scale_log2e, -m_safe));
+            const float p1 = fast_exp2(__builtin_fmaf(sv[j + 1], scale_log2e, -m_safe));
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            const bf16x2 pb = {(__bf16)p0, (__bf16)p1};
+            pf[j] = pb[0];
+            pf[j + 1] = pb[1];
+            const uint32_t bits = __builtin_bit_cast(uint32_t, pb);
+            psum += __uint_as_float(bits << 16) + __uint_as_float(bits & 0xFFFF0000u);
         }
     }
     st.l = st.l * alpha + psum;
