@@ -22,7 +22,12 @@
  *   scale: runtime float (1/16 for head dim 256);
  *   normalisation: RMSNorm, eps added to the mean square inside the root;
  *   fp8: OCP e4m3fn (bias 7, no infinity, 0x7F/0xFF are NaN, subnormals kept);
- *   one fp32 dequantisation scale per cached token per tensor.
+ *   one fp32 dequantisation scale per cached token per tensor;
+ *   4-bit storage (Section 5.2 discusses keeping the cache in 4 bits and
+ *   computing in 8; it names no format): OCP e2m1 elements (1 sign, 2 exponent
+ *   bits with bias 1, 1 fraction bit, subnormal kept, no infinity or NaN),
+ *   two per byte with the even element in the low four bits, and the same one
+ *   fp32 scale per token per tensor as the 8-bit record.
  *
  * Every floating point sum is carried in double.  Nothing is tiled, fused or
  * reordered: scores, maximum, exponentials, normaliser and weighted sum are
@@ -46,7 +51,7 @@
 
 #define ORACLE_API __attribute__((visibility("default")))
 
-enum { ORACLE_KV_BF16 = 0, ORACLE_KV_E4M3 = 1 };
+enum { ORACLE_KV_BF16 = 0, ORACLE_KV_E4M3 = 1, ORACLE_KV_E2M1 = 2 };
 
 /* ------------------------------------------------------------------ */
 /* Storage formats, decoded field by field.                            */
@@ -116,7 +121,19 @@ static uint16_t encode_bf16_rne(double x)
 }
 
 ORACLE_API double mfa_oracle_decode_bf16(uint16_t bits)   { return decode_bf16(bits); }
+/* e2m1 ("fp4"): 1 sign, 2 exponent bits (bias 1), 1 fraction bit.  Exponent field 0 is the
+ * subnormal binade (0 and 0.5); every code is a finite number. */
+static double decode_e2m1(uint8_t code)
+{
+    int sign = (code >> 3) & 1;
+    int expo = (code >> 1) & 3;
+    int frac = code & 1;
+    double mag = expo == 0 ? 0.5 * (double)frac : ldexp(1.0 + 0.5 * (double)frac, expo - 1);
+    return sign ? -mag : mag;
+}
+
 ORACLE_API double mfa_oracle_decode_e4m3fn(uint8_t bits)  { return decode_e4m3fn(bits); }
+ORACLE_API double mfa_oracle_decode_e2m1(uint8_t code)    { return decode_e2m1(code & 15); }
 ORACLE_API uint16_t mfa_oracle_encode_bf16(double x)      { return encode_bf16_rne(x); }
 
 /* ------------------------------------------------------------------ */
@@ -164,6 +181,11 @@ static double kv_elem(const kv_view *kv, const void *base, const float *scale, i
 {
     if (kv->kv_dtype == ORACLE_KV_BF16)
         return decode_bf16(((const uint16_t *)base)[row * kv->D + d]);
+    if (kv->kv_dtype == ORACLE_KV_E2M1) {
+        /* D/2 bytes per row; element d in byte d/2, low four bits when d is even */
+        uint8_t byte = ((const uint8_t *)base)[row * (kv->D / 2) + d / 2];
+        return (double)scale[row] * decode_e2m1((d & 1) ? (byte >> 4) : (byte & 15));
+    }
     return (double)scale[row] * decode_e4m3fn(((const uint8_t *)base)[row * kv->D + d]);
 }
 
@@ -242,8 +264,9 @@ ORACLE_API int mfa_oracle_decode_attn(const uint16_t *q, const void *k, const vo
                                       int64_t n_rows, const int32_t *row_b, const int32_t *row_h,
                                       float *out, double *lse)
 {
-    if (kv_dtype != ORACLE_KV_BF16 && kv_dtype != ORACLE_KV_E4M3) return 1;
-    if (kv_dtype == ORACLE_KV_E4M3 && (!k_scale || !v_scale)) return 1;
+    if (kv_dtype != ORACLE_KV_BF16 && kv_dtype != ORACLE_KV_E4M3 && kv_dtype != ORACLE_KV_E2M1) return 1;
+    if (kv_dtype != ORACLE_KV_BF16 && (!k_scale || !v_scale)) return 1;
+    if (kv_dtype == ORACLE_KV_E2M1 && (D & 1)) return 1;
     kv_view kv = { k, v, k_scale, v_scale, kv_dtype, D, seq_stride_tokens, NULL, 0, 0 };
     return run_rows(q, &kv, seq_lens, B, H, scale, n_rows, row_b, row_h, out, lse);
 }
@@ -258,8 +281,9 @@ ORACLE_API int mfa_oracle_decode_attn_paged(const uint16_t *q, const void *k_poo
                                             int64_t n_rows, const int32_t *row_b, const int32_t *row_h,
                                             float *out, double *lse)
 {
-    if (kv_dtype != ORACLE_KV_BF16 && kv_dtype != ORACLE_KV_E4M3) return 1;
-    if (kv_dtype == ORACLE_KV_E4M3 && (!k_scale_pool || !v_scale_pool)) return 1;
+    if (kv_dtype != ORACLE_KV_BF16 && kv_dtype != ORACLE_KV_E4M3 && kv_dtype != ORACLE_KV_E2M1) return 1;
+    if (kv_dtype != ORACLE_KV_BF16 && (!k_scale_pool || !v_scale_pool)) return 1;
+    if (kv_dtype == ORACLE_KV_E2M1 && (D & 1)) return 1;
     if (!block_table || page_size <= 0) return 1;
     kv_view kv = { k_pool, v_pool, k_scale_pool, v_scale_pool, kv_dtype, D, 0,
                    block_table, max_blocks_per_seq, page_size };
@@ -399,6 +423,47 @@ ORACLE_API int mfa_oracle_quantize_rows_e4m3(const float *x, int rows, int D, ui
             volatile float y = row[d] / scale;
             float c = y > 448.0f ? 448.0f : (y < -448.0f ? -448.0f : y);
             codes[(int64_t)r * D + d] = encode_e4m3fn_rne(c);
+        }
+    }
+    return 0;
+}
+
+/* Nearest e2m1 code of a finite float, ties to the code with an even fraction bit: the eight
+ * magnitudes are tried one after the other. */
+static uint8_t encode_e2m1_rne(float x)
+{
+    uint8_t sign = (uint8_t)(signbit(x) ? 8 : 0);
+    double a = fabs((double)x);
+    uint8_t best = 0;
+    double best_err = a;                             /* distance to magnitude 0 */
+    for (uint8_t c = 1; c < 8; ++c) {
+        double err = fabs(a - decode_e2m1(c));
+        if (err < best_err || (err == best_err && (c & 1) == 0)) { best = c; best_err = err; }
+    }
+    return (uint8_t)(sign | best);
+}
+
+/* 4-bit record of cache rows, the 8-bit record's recipe with e2m1's largest magnitude 6 in
+ * place of 448: scale = max(max_d |x_d|, 1e-12) / 6, code_d = e2m1(clamp(x_d / scale, -6, 6)),
+ * in single precision.  Packed two per byte, even d in the low four bits.  x: fp32 [rows, D],
+ * D even; packed: [rows, D/2]. */
+ORACLE_API int mfa_oracle_quantize_rows_e2m1(const float *x, int rows, int D, uint8_t *packed, float *scales)
+{
+    if (D & 1) return 1;
+    for (int r = 0; r < rows; ++r) {
+        const float *row = x + (int64_t)r * D;
+        float amax = 0.0f;
+        for (int d = 0; d < D; ++d) amax = fmaxf(amax, fabsf(row[d]));
+        volatile float scale = fmaxf(amax, 1e-12f) / 6.0f;
+        scales[r] = scale;
+        for (int d = 0; d < D; d += 2) {
+            uint8_t code[2];
+            for (int i = 0; i < 2; ++i) {
+                volatile float y = row[d + i] / scale;
+                float c = y > 6.0f ? 6.0f : (y < -6.0f ? -6.0f : y);
+                code[i] = encode_e2m1_rne(c);
+            }
+            packed[(int64_t)r * (D / 2) + d / 2] = (uint8_t)(code[0] | (code[1] << 4));
         }
     }
     return 0;

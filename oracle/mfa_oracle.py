@@ -14,6 +14,7 @@ from . import build as _build
 
 KV_BF16 = 0
 KV_E4M3 = 1
+KV_E2M1 = 2      # 4-bit e2m1 elements, two per byte: arrays are [..., D/2] uint8
 
 _lib = None
 
@@ -27,6 +28,8 @@ def lib():
         L.mfa_oracle_decode_bf16.argtypes = [ctypes.c_uint16]
         L.mfa_oracle_decode_e4m3fn.restype = ctypes.c_double
         L.mfa_oracle_decode_e4m3fn.argtypes = [ctypes.c_uint8]
+        L.mfa_oracle_decode_e2m1.restype = ctypes.c_double
+        L.mfa_oracle_decode_e2m1.argtypes = [ctypes.c_uint8]
         L.mfa_oracle_encode_bf16.restype = ctypes.c_uint16
         L.mfa_oracle_encode_bf16.argtypes = [ctypes.c_double]
         L.mfa_oracle_set_threads.argtypes = [ctypes.c_int]
@@ -74,6 +77,10 @@ def decode_e4m3fn(bits):
     return float(lib().mfa_oracle_decode_e4m3fn(int(bits)))
 
 
+def decode_e2m1(code):
+    return float(lib().mfa_oracle_decode_e2m1(int(code)))
+
+
 def encode_bf16(x):
     return int(lib().mfa_oracle_encode_bf16(float(x)))
 
@@ -89,7 +96,8 @@ def _rows(rows, B, H):
 
 def decode_attn(q, k, v, seq_lens, scale, k_scale=None, v_scale=None, kv_dtype=KV_BF16,
                 rows=None, return_lse=False):
-    """q uint16 [B,H,D]; k,v [B,S,D] uint16 (bf16) or uint8 (e4m3fn); scales fp32 [B,S].
+    """q uint16 [B,H,D]; k,v [B,S,D] uint16 (bf16) or uint8 (e4m3fn), or [B,S,D/2] uint8 (packed e2m1);
+    scales fp32 [B,S].
 
     rows: optional list of (b,h) pairs; then the result is [len(rows), D].
     Returns out fp32 [B,H,D] (or [n_rows,D]) and, if asked, lse float64.
@@ -99,7 +107,7 @@ def decode_attn(q, k, v, seq_lens, scale, k_scale=None, v_scale=None, kv_dtype=K
     kd = np.uint16 if kv_dtype == KV_BF16 else np.uint8
     k = _c(k, kd)
     v = _c(v, kd)
-    assert k.shape == v.shape and k.shape[0] == B and k.shape[2] == D
+    assert k.shape == v.shape and k.shape[0] == B and k.shape[2] == (D // 2 if kv_dtype == KV_E2M1 else D)
     S = k.shape[1]
     k_scale = _c(k_scale, np.float32)
     v_scale = _c(v_scale, np.float32)
@@ -128,7 +136,7 @@ def decode_attn_paged(q, k_pool, v_pool, block_table, seq_lens, scale, k_scale_p
     k_pool = _c(k_pool, kd)
     v_pool = _c(v_pool, kd)
     n_pages, page, D2 = k_pool.shape
-    assert D2 == D and v_pool.shape == k_pool.shape
+    assert D2 == (D // 2 if kv_dtype == KV_E2M1 else D) and v_pool.shape == k_pool.shape
     block_table = _c(np.asarray(block_table, dtype=np.int32), np.int32)
     assert block_table.shape[0] == B
     seq_lens = _c(np.asarray(seq_lens, dtype=np.int32), np.int32)
@@ -222,6 +230,17 @@ def quantize_rows_e4m3(x):
     rc = lib().mfa_oracle_quantize_rows_e4m3(_ptr(x), ctypes.c_int(rows), ctypes.c_int(D), _ptr(codes), _ptr(scales))
     assert rc == 0, rc
     return codes, scales
+
+
+def quantize_rows_e2m1(x):
+    """Per-row e2m1 quantisation in single precision: x float32 [rows, D] -> (packed uint8 [rows, D/2], scales float32 [rows])."""
+    x = _c(x, np.float32)
+    rows, D = x.shape
+    packed = np.empty((rows, D // 2), dtype=np.uint8)
+    scales = np.empty((rows,), dtype=np.float32)
+    rc = lib().mfa_oracle_quantize_rows_e2m1(_ptr(x), ctypes.c_int(rows), ctypes.c_int(D), _ptr(packed), _ptr(scales))
+    assert rc == 0, rc
+    return packed, scales
 
 
 def round_bf16(x):

@@ -40,7 +40,7 @@ class AttnCase:
     name: str
     q: torch.Tensor                      # bf16 [B,H,D]
     seq_lens: torch.Tensor               # int32 [B]
-    kv_dtype: str                        # "bf16" | "fp8"
+    kv_dtype: str                        # "bf16" | "fp8" | "fp4" (e2m1, two per byte: [..., D/2] uint8)
     # contiguous cache
     k: Optional[torch.Tensor] = None     # [B,S,D]
     v: Optional[torch.Tensor] = None
@@ -80,8 +80,31 @@ def quantize_e4m3_per_token(x):
     return y.to(torch.float8_e4m3fn), scale.contiguous()
 
 
+E2M1_MAX = 6.0
+
+
+def quantize_e2m1_per_token(x):
+    """fp32 [..., D] -> (e2m1 codes packed two per byte [..., D/2] uint8, fp32 scales [...]): one scale per
+    row, nearest grid value with ties to the even code, element 2i in the low four bits of byte i."""
+    amax = x.abs().amax(dim=-1)
+    scale = torch.clamp(amax, min=1e-12) / E2M1_MAX
+    y = (x / scale.unsqueeze(-1)).clamp_(-E2M1_MAX, E2M1_MAX)
+    a = y.abs()
+    code = torch.zeros_like(a, dtype=torch.uint8)
+    # midpoints between neighbouring magnitudes 0, .5, 1, 1.5, 2, 3, 4, 6; a tie goes to the even code
+    for mid, tie_goes_up in ((0.25, False), (0.75, True), (1.25, False), (1.75, True), (2.5, False), (3.5, True),
+                             (5.0, False)):
+        code += ((a >= mid) if tie_goes_up else (a > mid)).to(torch.uint8)
+    code |= torch.signbit(y).to(torch.uint8) << 3
+    packed = code[..., 0::2] | (code[..., 1::2] << 4)
+    return packed.contiguous(), scale.contiguous()
+
+
 def _nan_like(t):
-    """A tensor of t's shape and dtype full of NaN codes."""
+    """A tensor of t's shape and dtype full of NaN codes (packed 4-bit codes have no NaN: all ones, and the
+    scale beside them is NaN)."""
+    if t.dtype == torch.uint8:
+        return torch.full(t.shape, 0xFF, dtype=torch.uint8)
     if t.dtype == torch.float8_e4m3fn:
         return torch.full(t.shape, 0x7F, dtype=torch.uint8).view(torch.float8_e4m3fn)
     return torch.full(t.shape, float("nan"), dtype=t.dtype)
@@ -115,6 +138,9 @@ def make_contiguous_case(name, seed, B, S, seq_lens=None, kv_dtype="bf16", poiso
     elif kv_dtype == "fp8":
         case.k, case.k_scale = quantize_e4m3_per_token(k32)
         case.v, case.v_scale = quantize_e4m3_per_token(v32)
+    elif kv_dtype == "fp4":
+        case.k, case.k_scale = quantize_e2m1_per_token(k32)
+        case.v, case.v_scale = quantize_e2m1_per_token(v32)
     else:
         raise ValueError(kv_dtype)
     if poison:
@@ -168,6 +194,9 @@ def make_paged_case(name, seed, seq_lens, kv_dtype="bf16", poison=True, spare_pa
     elif kv_dtype == "fp8":
         case.k_pool, case.k_scale_pool = quantize_e4m3_per_token(k32)
         case.v_pool, case.v_scale_pool = quantize_e4m3_per_token(v32)
+    elif kv_dtype == "fp4":
+        case.k_pool, case.k_scale_pool = quantize_e2m1_per_token(k32)
+        case.v_pool, case.v_scale_pool = quantize_e2m1_per_token(v32)
     else:
         raise ValueError(kv_dtype)
     if poison:
@@ -190,7 +219,7 @@ def paged_to_contiguous(case: AttnCase, S=None, poison=True) -> AttnCase:
                    kv_dtype=case.kv_dtype, scale=case.scale)
     out.k = _nan_like(torch.empty(B, S, D, dtype=case.k_pool.dtype)) if poison else torch.zeros(B, S, D, dtype=case.k_pool.dtype)
     out.v = out.k.clone()
-    if case.kv_dtype == "fp8":
+    if case.kv_dtype != "bf16":
         out.k_scale = torch.full((B, S), float("nan") if poison else 1.0, dtype=torch.float32)
         out.v_scale = out.k_scale.clone()
     for b in range(B):
@@ -200,7 +229,7 @@ def paged_to_contiguous(case: AttnCase, S=None, poison=True) -> AttnCase:
             p = int(case.block_table[b, i])
             out.k[b, i * page:i * page + n] = case.k_pool[p, :n]
             out.v[b, i * page:i * page + n] = case.v_pool[p, :n]
-            if case.kv_dtype == "fp8":
+            if case.kv_dtype != "bf16":
                 out.k_scale[b, i * page:i * page + n] = case.k_scale_pool[p, :n]
                 out.v_scale[b, i * page:i * page + n] = case.v_scale_pool[p, :n]
     return out
