@@ -63,7 +63,8 @@ typedef enum {
 
 typedef enum {
     MFA_KV_BF16 = 0,
-    MFA_KV_FP8_E4M3 = 1                  /* one fp32 scale per token per tensor             */
+    MFA_KV_FP8_E4M3 = 1,                 /* one fp32 scale per token per tensor             */
+    MFA_KV_FP4_E2M1 = 2                  /* 4-bit elements, two per byte; scales as for fp8 */
 } mfa_kv_dtype;
 
 /* Problem description fixed at init (Section 2, model-card table, gives the
@@ -124,6 +125,9 @@ MFA_API mfa_status mfa_query_proj(mfa_ctx* ctx, const void* x, const void* w_qa,
  *     fp8 cache:  per token and tensor  scale = max(max_d |x_d|, 1e-12) / 448,
  *                 code_d = e4m3(clamp(x_d / scale, -448, 448)),  scale stored beside the row;
  *                 single precision throughout, so the codes depend on the fp32 row alone
+ *     fp4 cache:  the same with 6, e2m1's largest magnitude, in place of 448 and
+ *                 code_d = e2m1(...) rounded to nearest, ties to the even code; codes of
+ *                 elements 2i and 2i+1 in byte i, the even one in the low four bits
  *   x        bf16 [B, d_model]
  *   w_kv     bf16 [d_model, 2*head_dim]  (in x out; key columns first, then value columns)
  *   k_cache, v_cache, k_scale, v_scale, kv_seq_stride_tokens, seq_lens: as for
@@ -168,10 +172,14 @@ MFA_API mfa_status mfa_out_proj(mfa_ctx* ctx, const float* attn_out, const void*
  *     p[b,h,:] = softmax_j(s[b,h,:])
  *     out[b,h,d] = sum_j p[b,h,j] * V[b,j,d]
  * with K[b,j,:] = k_cache[b,j,:] for bf16 and k_scale[b,j] * k_cache[b,j,:] for
- * fp8 (V likewise).
+ * fp8 and fp4 (V likewise).  MFA_KV_FP4_E2M1 is the "4-bit storage, 8-bit
+ * arithmetic" cache that Section 5.2 discusses: a row is head_dim/2 bytes, element
+ * d in byte d/2 (low four bits when d is even) as an e2m1 code (1 sign, 2 exponent
+ * bits with bias 1, 1 fraction bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives),
+ * with the same per-token fp32 scales as fp8.
  *   q        bf16 [B, n_q_heads, head_dim]
- *   k_cache, v_cache  [B, kv_seq_stride_tokens, head_dim] in kv_dtype
- *   k_scale, v_scale  fp32 [B, kv_seq_stride_tokens]; NULL unless fp8
+ *   k_cache, v_cache  [B, kv_seq_stride_tokens, head_dim] in kv_dtype (fp4: head_dim/2 bytes per row)
+ *   k_scale, v_scale  fp32 [B, kv_seq_stride_tokens]; NULL for bf16
  *   kv_seq_stride_tokens  rows between consecutive sequences (>= max_seq_len_hint)
  *   seq_lens int32 [B] on the DEVICE (never read by the host)
  *   max_seq_len_hint  host-side upper bound of seq_lens, used only to size the
@@ -195,8 +203,8 @@ MFA_API mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_ca
 /*
  * The same attention over a paged cache: token j of sequence b is row
  * (j % page_size) of page block_table[b][j / page_size].
- *   k_pool, v_pool            [n_pages, page_size, head_dim] in kv_dtype
- *   k_scale_pool, v_scale_pool  fp32 [n_pages, page_size]; NULL unless fp8
+ *   k_pool, v_pool            [n_pages, page_size, head_dim] in kv_dtype (fp4: head_dim/2 bytes per row)
+ *   k_scale_pool, v_scale_pool  fp32 [n_pages, page_size]; NULL for bf16
  *   block_table  int32 [B, max_blocks_per_seq] on the device; entries at or past
  *                ceil(seq_lens[b] / page_size) are never read (may be -1)
  *   max_blocks_per_seq >= ceil(max_seq_len_hint / page_size)

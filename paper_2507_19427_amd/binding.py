@@ -21,6 +21,7 @@ MFA_ERR_HIP = 4
 
 MFA_KV_BF16 = 0
 MFA_KV_FP8_E4M3 = 1
+MFA_KV_FP4_E2M1 = 2
 
 EXPORTS = [
     "mfa_decode_workspace_bytes", "mfa_decode_init", "mfa_decode_destroy", "mfa_status_string",
@@ -140,7 +141,14 @@ def _kv_dtype(t):
         return MFA_KV_BF16
     if t.dtype == torch.float8_e4m3fn:
         return MFA_KV_FP8_E4M3
+    if t.dtype == torch.uint8:                       # e2m1 codes, two per byte: last dimension head_dim / 2
+        return MFA_KV_FP4_E2M1
     raise TypeError(f"unsupported cache dtype {t.dtype}")
+
+
+def _cache_width(cfg, kvd):
+    """Last dimension of a cache tensor: elements per row, or bytes for the packed 4-bit record."""
+    return cfg.head_dim // 2 if kvd == MFA_KV_FP4_E2M1 else cfg.head_dim
 
 
 def _want(t, dtype, name):
@@ -222,8 +230,9 @@ def mfa_decode_attn(ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_
     if v_cache.dtype != k_cache.dtype or not k_cache.is_contiguous() or not v_cache.is_contiguous():
         raise TypeError("k_cache / v_cache must be contiguous and of one dtype")
     S = k_cache.shape[1]
-    if tuple(q.shape) != (B, cfg.n_q_heads, cfg.head_dim) or tuple(k_cache.shape) != (B, S, cfg.head_dim) or \
-            tuple(v_cache.shape) != (B, S, cfg.head_dim) or tuple(seq_lens.shape) != (B,):
+    width = _cache_width(cfg, kvd)
+    if tuple(q.shape) != (B, cfg.n_q_heads, cfg.head_dim) or tuple(k_cache.shape) != (B, S, width) or \
+            tuple(v_cache.shape) != (B, S, width) or tuple(seq_lens.shape) != (B,):
         raise ValueError("attention shapes do not match")
     for t, nm in ((k_scale, "k_scale"), (v_scale, "v_scale")):
         if t is not None:
@@ -252,7 +261,7 @@ def mfa_decode_attn_paged(ctx: MfaContext, q, k_pool, v_pool, block_table, seq_l
     if v_pool.dtype != k_pool.dtype or not k_pool.is_contiguous() or not v_pool.is_contiguous():
         raise TypeError("k_pool / v_pool must be contiguous and of one dtype")
     n_pages = k_pool.shape[0]
-    if tuple(k_pool.shape) != (n_pages, cfg.page_size, cfg.head_dim) or tuple(v_pool.shape) != tuple(k_pool.shape) \
+    if tuple(k_pool.shape) != (n_pages, cfg.page_size, _cache_width(cfg, kvd)) or tuple(v_pool.shape) != tuple(k_pool.shape) \
             or block_table.shape[0] != B or tuple(seq_lens.shape) != (B,) or \
             tuple(q.shape) != (B, cfg.n_q_heads, cfg.head_dim):
         raise ValueError("paged attention shapes do not match")
@@ -285,8 +294,9 @@ def mfa_decode_attn_multi(ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_se
     if v_cache.dtype != k_cache.dtype or not k_cache.is_contiguous() or not v_cache.is_contiguous():
         raise TypeError("k_cache / v_cache must be contiguous and of one dtype")
     S = k_cache.shape[1]
-    if tuple(q.shape) != (B, q_len, cfg.n_q_heads, cfg.head_dim) or tuple(k_cache.shape) != (B, S, cfg.head_dim) or \
-            tuple(v_cache.shape) != (B, S, cfg.head_dim) or tuple(seq_lens.shape) != (B,):
+    width = _cache_width(cfg, kvd)
+    if tuple(q.shape) != (B, q_len, cfg.n_q_heads, cfg.head_dim) or tuple(k_cache.shape) != (B, S, width) or \
+            tuple(v_cache.shape) != (B, S, width) or tuple(seq_lens.shape) != (B,):
         raise ValueError("attention shapes do not match")
     for t, nm in ((k_scale, "k_scale"), (v_scale, "v_scale")):
         if t is not None:
@@ -319,7 +329,7 @@ def mfa_decode_attn_paged_multi(ctx: MfaContext, q, k_pool, v_pool, block_table,
     if v_pool.dtype != k_pool.dtype or not k_pool.is_contiguous() or not v_pool.is_contiguous():
         raise TypeError("k_pool / v_pool must be contiguous and of one dtype")
     n_pages = k_pool.shape[0]
-    if tuple(k_pool.shape) != (n_pages, cfg.page_size, cfg.head_dim) or tuple(v_pool.shape) != tuple(k_pool.shape) \
+    if tuple(k_pool.shape) != (n_pages, cfg.page_size, _cache_width(cfg, kvd)) or tuple(v_pool.shape) != tuple(k_pool.shape) \
             or block_table.shape[0] != B or tuple(seq_lens.shape) != (B,) or \
             tuple(q.shape) != (B, q_len, cfg.n_q_heads, cfg.head_dim):
         raise ValueError("paged attention shapes do not match")
@@ -387,7 +397,8 @@ def mfa_kv_append(ctx: MfaContext, x, w_kv, k_cache, v_cache, seq_lens, k_scale=
     _want(seq_lens, torch.int32, "seq_lens")
     B = x.shape[0]
     if tuple(x.shape) != (B, cfg.d_model) or tuple(w_kv.shape) != (cfg.d_model, 2 * cfg.head_dim) or \
-            k_cache.dim() != 3 or k_cache.shape[0] != B or k_cache.shape[2] != cfg.head_dim or tuple(seq_lens.shape) != (B,):
+            k_cache.dim() != 3 or k_cache.shape[0] != B or k_cache.shape[2] != _cache_width(cfg, _kv_dtype(k_cache)) or \
+            tuple(seq_lens.shape) != (B,):
         raise ValueError("kv append shapes do not match")
     kvd = _check_cache_pair(k_cache, v_cache, k_scale, v_scale, k_cache.shape[:2])
     _check(lib().mfa_kv_append(ctx.handle, _ptr(x), _ptr(w_kv), kvd, _ptr(k_cache), _ptr(v_cache), _ptr(k_scale),
@@ -405,8 +416,8 @@ def mfa_kv_append_paged(ctx: MfaContext, x, w_kv, k_pool, v_pool, block_table, s
     B = x.shape[0]
     n_pages = k_pool.shape[0]
     if tuple(x.shape) != (B, cfg.d_model) or tuple(w_kv.shape) != (cfg.d_model, 2 * cfg.head_dim) or \
-            tuple(k_pool.shape) != (n_pages, cfg.page_size, cfg.head_dim) or block_table.shape[0] != B or \
-            tuple(seq_lens.shape) != (B,):
+            tuple(k_pool.shape) != (n_pages, cfg.page_size, _cache_width(cfg, _kv_dtype(k_pool))) or \
+            block_table.shape[0] != B or tuple(seq_lens.shape) != (B,):
         raise ValueError("paged kv append shapes do not match")
     kvd = _check_cache_pair(k_pool, v_pool, k_scale_pool, v_scale_pool, k_pool.shape[:2])
     _check(lib().mfa_kv_append_paged(ctx.handle, _ptr(x), _ptr(w_kv), kvd, _ptr(k_pool), _ptr(v_pool), _ptr(k_scale_pool),

@@ -117,8 +117,8 @@ mfa_status check_attn_common(const mfa_ctx* ctx, const void* q, const void* k, c
                              int32_t B, const float* out)
 {
     if (!ctx || !q || !k || !v || !seq_lens || !out) return MFA_ERR_INVALID_ARG;
-    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return MFA_ERR_INVALID_ARG;
-    if (kv_dtype == MFA_KV_FP8_E4M3 && (!ks || !vs)) return MFA_ERR_INVALID_ARG;
+    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3 && kv_dtype != MFA_KV_FP4_E2M1) return MFA_ERR_INVALID_ARG;
+    if (kv_dtype != MFA_KV_BF16 && (!ks || !vs)) return MFA_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(ks) || !aligned16(vs) ||
         (reinterpret_cast<uintptr_t>(seq_lens) & 3u))
         return MFA_ERR_INVALID_ARG;
@@ -263,8 +263,8 @@ mfa_status check_kv_append(const mfa_ctx* ctx, const void* x, const void* w_kv, 
                            const void* v, const float* ks, const float* vs, const int32_t* seq_lens, int32_t B)
 {
     if (!ctx || !x || !w_kv || !k || !v || !seq_lens) return MFA_ERR_INVALID_ARG;
-    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return MFA_ERR_INVALID_ARG;
-    if (kv_dtype == MFA_KV_FP8_E4M3 && (!ks || !vs)) return MFA_ERR_INVALID_ARG;
+    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3 && kv_dtype != MFA_KV_FP4_E2M1) return MFA_ERR_INVALID_ARG;
+    if (kv_dtype != MFA_KV_BF16 && (!ks || !vs)) return MFA_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(w_kv) || !aligned16(k) || !aligned16(v) || !aligned16(ks) || !aligned16(vs) ||
         (reinterpret_cast<uintptr_t>(seq_lens) & 3u))
         return MFA_ERR_INVALID_ARG;

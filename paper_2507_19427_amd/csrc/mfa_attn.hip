@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
         if (!first_segment) __syncthreads();          // the previous segment's exchange area is the tile memory
         first_segment = false;
 
-        QFrags<false> q;
+        QFrags<16> q;
         load_q_fragments(q.f, a.q, QL == 2 ? 2 * r.b + grp : r.b, 16 * wq + n, g);
         const int t1_mine = QL == 2 ? (r.t1 < r.len - 1 + grp ? r.t1 : r.len - 1 + grp) : r.t1;   // grp = query token when QL == 2
 
@@ -118,12 +118,12 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int unit = slot * kSlotBytes + u * kUnitBytes;
-                    process_unit<false>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + u * kUnitTokens,
+                    process_unit<16>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + u * kUnitTokens,
                                         t1_mine, a.scale_log2e, n, g, 0, 0);
                 }
             } else {
                 const int unit = slot * kSlotBytes + grp * kUnitBytes;
-                process_unit<false>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + grp * kUnitTokens,
+                process_unit<16>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + grp * kUnitTokens,
                                     t1_mine, a.scale_log2e, n, g, 0, 0);
             }
         }
@@ -132,15 +132,18 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     }
 }
 
-// ---- fp8 cache.
-// Keys stay e4m3 codes all the way: each tile's 16 KB go by direct loads into a ring of three LDS
-// slots and are multiplied on the fp8 MFMA against the two-term query.  Values are multiplied by
-// bf16 weights, so their codes are converted once per tile: every thread carries two 16-byte pieces
-// of V and one per-token scale in registers from HBM, converts (exactly: every e4m3 value is a bf16
-// value) and writes the swizzled bf16 rows into one of two value images.
+// ---- 8-bit and 4-bit caches (BITS = 8: e4m3 codes, 256 B per row; BITS = 4: e2m1 codes two per byte,
+// 128 B per row; one fp32 scale per token and tensor beside either).
+// Keys stay codes all the way: each tile's rows go by direct loads into a ring of three LDS slots and
+// are multiplied on the fp8/fp4 MFMA against the two-term query.  Values are multiplied by bf16
+// weights, so their codes are converted once per tile: every thread carries 32 bytes (8 bit: two
+// 16-byte pieces; 4 bit: one) of V and one per-token scale in registers from HBM, converts (exactly:
+// every e4m3 and e2m1 value is a bf16 value) and writes the swizzled bf16 rows into one of two value
+// images.
 //
 // LDS: value image P (P = tile & 1) at P*32 KB, its unit g at + g*16 KB; key slot k (tile % 3) at
-// 64 KB + k*16 KB; scale set P at 112 KB + P*512 B (64 key scales, then 64 value scales).
+// 64 KB + k*16 KB (4 bit: the first 8 KB of it); scale set P at 112 KB + P*512 B (64 key scales, then
+// 64 value scales).
 constexpr int kFp8VImageBytes = 2 * 16384;
 constexpr int kFp8KBase = 2 * kFp8VImageBytes;
 constexpr int kFp8KSlotBytes = kTile * 256;
@@ -151,15 +154,17 @@ static_assert(kFp8LdsBytes <= kSchedLdsOffset && kAttnLdsBytes <= kSchedLdsOffse
               "the schedule's prefix sums live behind the tile memory of both kernels");
 
 struct Fp8TileRegs {
-    u32x4 piece[2];       // V rows prow and prow + 32, 16-byte chunk pchunk
+    u32x4 piece[2];       // 8 bit: V rows prow and prow + 32, 16-byte chunk pchunk; 4 bit: piece[0] only,
+                          // V row tid / 8, 16-byte chunk tid % 8 (32 elements)
     float scale;          // threads 0..63: key scale of token tid; 64..127: value scale of token tid - 64
 };
-// Every step of the pipeline issues, per wave and in this order, the three register loads of a
-// tile and the two direct loads of a key tile.  They are inline assembly, awaited with an explicit
-// vmcnt that leaves exactly the youngest step's five in flight: left to the compiler, the wait would
-// be widened to vmcnt(0) at the loop's control-flow joins and drain the pipeline every tile.  The
-// registers pass through the waiting statement, so no use of them can be scheduled before it.
-constexpr int kFp8OpsPerStep = 5;
+// Every step of the pipeline issues, per wave and in this order, the register loads of a tile
+// (8 bit: two pieces and a scale; 4 bit: one piece and a scale) and the direct loads of a key tile
+// (8 bit: two; 4 bit: one).  They are inline assembly, awaited with an explicit vmcnt that leaves
+// exactly the youngest step's loads in flight: left to the compiler, the wait would be widened to
+// vmcnt(0) at the loop's control-flow joins and drain the pipeline every tile.  The registers pass
+// through the waiting statement, so no use of them can be scheduled before it.
+template <int BITS> constexpr int kLowbitOpsPerStep = BITS == 8 ? 5 : 3;
 __device__ __forceinline__ void load_regs_16B(u32x4& dst, const void* p)
 {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
@@ -168,22 +173,32 @@ __device__ __forceinline__ void load_regs_4B(float& dst, const void* p)
 {
     asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
 }
+template <int BITS>
 __device__ __forceinline__ void wait_all_but_youngest_step(Fp8TileRegs& t)
 {
-    static_assert(kFp8OpsPerStep == 5, "the wait below leaves 5 operations in flight");
-    asm volatile("s_waitcnt vmcnt(5)" : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.scale) :: "memory");
+    if constexpr (BITS == 8) {
+        static_assert(kLowbitOpsPerStep<8> == 5, "the wait below leaves 5 operations in flight");
+        asm volatile("s_waitcnt vmcnt(5)" : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.scale) :: "memory");
+    } else {
+        static_assert(kLowbitOpsPerStep<4> == 3, "the wait below leaves 3 operations in flight");
+        asm volatile("s_waitcnt vmcnt(3)" : "+v"(t.piece[0]), "+v"(t.scale) :: "memory");
+    }
 }
 // Wait for every load in flight while both register sets are still owned by the pipeline: no
 // register of theirs may be handed to other code before its load has landed.
+template <int BITS>
 __device__ __forceinline__ void drain_tiles(Fp8TileRegs& t, Fp8TileRegs& u)
 {
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.scale), "+v"(u.piece[0]), "+v"(u.piece[1]), "+v"(u.scale)
-                 :: "memory");
+    if constexpr (BITS == 8)
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(t.piece[0]), "+v"(t.piece[1]), "+v"(t.scale), "+v"(u.piece[0]), "+v"(u.piece[1]), "+v"(u.scale)
+                     :: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(t.piece[0]), "+v"(t.scale), "+v"(u.piece[0]), "+v"(u.scale) :: "memory");
 }
 
-template <bool PAGED, int QL>
-__global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
+template <bool PAGED, int QL, int BITS>
+__global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const lds_ptr_t lds_base = (lds_ptr_t)smem;
@@ -205,8 +220,9 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
 
         // Tiles past the end of the segment repeat its last tile (never consumed), so that every step
         // issues the same number of loads.  Rows at or past t1 re-read the last valid token.
-        const int prow = threadIdx.x >> 4;
-        const int pchunk = threadIdx.x & 15;
+        constexpr int kRowBytes = BITS == 8 ? 256 : 128;                   // one cached row of K or V
+        const int prow = BITS == 8 ? threadIdx.x >> 4 : threadIdx.x >> 3;  // 8 bit: 0..31 (and + 32); 4 bit: 0..63
+        const int pchunk = BITS == 8 ? threadIdx.x & 15 : threadIdx.x & 7; // 16-byte chunk of the row
         auto tile_origin = [&](int tile, int& tile_t0, int64_t& row0, int& last) {
             if (tile >= r.n_tiles) tile = r.n_tiles - 1;
             tile = __builtin_amdgcn_readfirstlane(tile);                   // keeps the page lookup a scalar load
@@ -218,47 +234,76 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
             int tile_t0, last; int64_t row0;
             tile_origin(tile, tile_t0, row0, last);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < (BITS == 8 ? 2 : 1); ++i) {
                 const int row = prow + 32 * i;
                 const int in_tile = row > last ? last : row;
-                load_regs_16B(t.piece[i], (const unsigned char*)a.v + (size_t)(row0 + in_tile) * 256 + pchunk * 16);
+                load_regs_16B(t.piece[i], (const unsigned char*)a.v + (size_t)(row0 + in_tile) * kRowBytes + pchunk * 16);
             }
             const int tok = threadIdx.x & 63;                              // threads 128.. repeat those of 0..127
             const int in_tile = tok > last ? last : tok;
             load_regs_4B(t.scale, ((threadIdx.x & 64) ? a.v_scale : a.k_scale) + (row0 + in_tile));
         };
-        // Keys of a tile: 16 direct loads of 4 rows; wave w issues loads 2w and 2w + 1.
+        // Keys of a tile.  8 bit: 16 direct loads of 4 rows, wave w issues loads 2w and 2w + 1, 16-byte
+        // chunk c of row r lands at c ^ (r & 15).  4 bit: 8 direct loads of 8 rows, one per wave, chunk c
+        // of row r lands at c ^ ((r >> 1) & 7): 16 consecutive rows then spread one chunk column over all
+        // 64 banks.
         auto issue_keys = [&](int tile, int kslot) {
             int tile_t0, last; int64_t row0;
             tile_origin(tile, tile_t0, row0, last);
+            if constexpr (BITS == 8) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int first_row = 4 * (2 * wave + i);                     // wave-uniform
-                const int row = first_row + (lane >> 4);
+                for (int i = 0; i < 2; ++i) {
+                    const int first_row = 4 * (2 * wave + i);                     // wave-uniform
+                    const int row = first_row + (lane >> 4);
+                    const int in_tile = row > last ? last : row;
+                    const int c16 = (lane & 15) ^ (row & 15);
+                    load_to_lds_16B((const unsigned char*)a.k + (size_t)(row0 + in_tile) * 256 + c16 * 16,
+                                    lds_addr0 + kFp8KBase + kslot * kFp8KSlotBytes + first_row * 256);
+                }
+            } else {
+                const int first_row = 8 * wave;                                   // wave-uniform
+                const int row = first_row + (lane >> 3);
                 const int in_tile = row > last ? last : row;
-                const int c16 = (lane & 15) ^ (row & 15);
-                load_to_lds_16B((const unsigned char*)a.k + (size_t)(row0 + in_tile) * 256 + c16 * 16,
-                                lds_addr0 + kFp8KBase + kslot * kFp8KSlotBytes + first_row * 256);
+                const int c16 = (lane & 7) ^ ((row >> 1) & 7);
+                load_to_lds_16B((const unsigned char*)a.k + (size_t)(row0 + in_tile) * 128 + c16 * 16,
+                                lds_addr0 + kFp8KBase + kslot * kFp8KSlotBytes + first_row * 128);
             }
         };
         // Convert a tile's value codes to bf16 and write them into image `image`; the scales go beside it.
         auto store_tile = [&](const Fp8TileRegs& t, int image) {
+            if constexpr (BITS == 8) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                bf16x8 half[2];
+                for (int i = 0; i < 2; ++i) {
+                    bf16x8 half[2];
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], false);
-                    const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], true);
-                    half[w >> 1][4 * (w & 1) + 0] = (__bf16)f01[0];
-                    half[w >> 1][4 * (w & 1) + 1] = (__bf16)f01[1];
-                    half[w >> 1][4 * (w & 1) + 2] = (__bf16)f23[0];
-                    half[w >> 1][4 * (w & 1) + 3] = (__bf16)f23[1];
+                    for (int w = 0; w < 4; ++w) {
+                        const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], false);
+                        const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], true);
+                        half[w >> 1][4 * (w & 1) + 0] = (__bf16)f01[0];
+                        half[w >> 1][4 * (w & 1) + 1] = (__bf16)f01[1];
+                        half[w >> 1][4 * (w & 1) + 2] = (__bf16)f23[0];
+                        half[w >> 1][4 * (w & 1) + 3] = (__bf16)f23[1];
+                    }
+                    const int key = prow & 15;                                 // row within its unit = prow (0..31)
+                    const int off = image * kFp8VImageBytes + i * 16384 + prow * 512 + ((pchunk ^ key) << 5);
+                    *LDS_AT(bf16x8, lds_base, off) = half[0];
+                    *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
                 }
-                const int key = prow & 15;                                 // row within its unit = prow (0..31)
-                const int off = image * kFp8VImageBytes + i * 16384 + prow * 512 + ((pchunk ^ key) << 5);
-                *LDS_AT(bf16x8, lds_base, off) = half[0];
-                *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
+            } else {
+                // 32 elements = bf16 chunks 2*pchunk and 2*pchunk + 1 (32 bytes each) of row prow
+                const int key = prow & 15;
+                const int row_off = image * kFp8VImageBytes + (prow >> 5) * 16384 + (prow & 31) * 512;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {                                  // word w: elements 8w .. 8w + 7
+                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                    const bf16x2 p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 0);
+                    const bf16x2 p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 1);
+                    const bf16x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 2);
+                    const bf16x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 3);
+                    const bf16x8 eight = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+                    const int chunk = 2 * pchunk + (w >> 1);
+                    *LDS_AT(bf16x8, lds_base, row_off + ((chunk ^ key) << 5) + (w & 1) * 16) = eight;
+                }
             }
             if (threadIdx.x < 128) *LDS_AT(float, lds_base, kFp8ScaleBase + image * 512 + threadIdx.x * 4) = t.scale;
         };
@@ -275,11 +320,11 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
         issue_keys(0, 0);
         // The query fragments are loaded by ordinary loads: the compiler completes them, and with them
         // everything above, right here instead of inside the loop.
-        QFrags<true> q;
-        load_split_q_fp8(q, a.q, QL == 2 ? 2 * r.b + grp : r.b, 16 * wq + n, g);
+        QFrags<BITS> q;
+        load_split_q<BITS>(q, a.q, QL == 2 ? 2 * r.b + grp : r.b, 16 * wq + n, g);
         const int t1_mine = QL == 2 ? (r.t1 < r.len - 1 + grp ? r.t1 : r.len - 1 + grp) : r.t1;   // grp = query token when QL == 2
         asm volatile("" : "+v"(q.hi[0]), "+v"(q.hi[1]), "+v"(q.lo[0]), "+v"(q.lo[1]));
-        drain_tiles(regs[0], regs[1]);
+        drain_tiles<BITS>(regs[0], regs[1]);
         store_tile(regs[0], 0);
         load_tile(regs[0], 2);
         issue_keys(1, 1);
@@ -287,14 +332,14 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
         int kslot = 0;                                                     // t % 3
         auto step = [&](auto parity_c, int t) {
             constexpr int P = decltype(parity_c)::value;                    // t & 1
-            wait_all_but_youngest_step(regs[P ^ 1]);       // registers of tile t+1 and keys of tile t have landed
+            wait_all_but_youngest_step<BITS>(regs[P ^ 1]);       // registers of tile t+1 and keys of tile t have landed
             __syncthreads();                               // ... for every wave; everyone is done with tile t-1
             store_tile(regs[P ^ 1], P ^ 1);                                 // values of tile t+1
             load_tile(regs[P ^ 1], t + 3);
             issue_keys(t + 2, kslot == 0 ? 2 : kslot - 1);                  // (t + 2) % 3, the slot tile t-1 has left
             auto unit = [&](int u) {
                 const int scales = kFp8ScaleBase + P * 512 + u * kUnitTokens * 4;
-                process_unit<true>(st, q, lds_base, kFp8KBase + kslot * kFp8KSlotBytes + u * kUnitTokens * 256,
+                process_unit<BITS>(st, q, lds_base, kFp8KBase + kslot * kFp8KSlotBytes + u * kUnitTokens * kRowBytes,
                                    P * kFp8VImageBytes + u * 16384, r.t0 + t * kTile + u * kUnitTokens, t1_mine,
                                    a.scale_log2e, n, g, scales, scales + 256);
             };
@@ -307,7 +352,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_fp8_kernel(AttnArgs a)
             if (t + 1 >= r.n_tiles) break;
             step(std::integral_constant<int, 1>{}, t + 1);
         }
-        drain_tiles(regs[0], regs[1]);        // the repeats of the last tile issued past the end
+        drain_tiles<BITS>(regs[0], regs[1]);  // the repeats of the last tile issued past the end
         if (QL == 2) finish_segment_two(st, a, r, grp, wq, lane);
         else         finish_segment(st, lds_base, a, r, wq, grp, lane);
     }
@@ -456,16 +501,17 @@ template <int QL>
 const void* attn_kernel(mfa_kv_dtype kv_dtype, bool paged)
 {
     if (kv_dtype == MFA_KV_BF16) return paged ? (const void*)decode_bf16_kernel<true, QL> : (const void*)decode_bf16_kernel<false, QL>;
-    return paged ? (const void*)decode_fp8_kernel<true, QL> : (const void*)decode_fp8_kernel<false, QL>;
+    if (kv_dtype == MFA_KV_FP4_E2M1) return paged ? (const void*)decode_lowbit_kernel<true, QL, 4> : (const void*)decode_lowbit_kernel<false, QL, 4>;
+    return paged ? (const void*)decode_lowbit_kernel<true, QL, 8> : (const void*)decode_lowbit_kernel<false, QL, 8>;
 }
 
 }  // namespace
 
 hipError_t prepare_decode_attn_kernels()
 {
-    for (int dt = 0; dt < 2; ++dt)
+    for (int dt = 0; dt < 3; ++dt)
         for (int paged = 0; paged < 2; ++paged) {
-            const mfa_kv_dtype kvd = dt ? MFA_KV_FP8_E4M3 : MFA_KV_BF16;
+            const mfa_kv_dtype kvd = dt == 0 ? MFA_KV_BF16 : (dt == 1 ? MFA_KV_FP8_E4M3 : MFA_KV_FP4_E2M1);
             hipError_t e = hipFuncSetAttribute(attn_kernel<1>(kvd, paged != 0), hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
             if (e != hipSuccess) return e;
             e = hipFuncSetAttribute(attn_kernel<2>(kvd, paged != 0), hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
@@ -479,7 +525,7 @@ hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStrea
 {
     const dim3 grid((unsigned)(a.n_wgs > 0 ? a.n_wgs : a.B * a.n_splits));
     const dim3 block(kAttnThreads);
-    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3) return hipErrorNotSupported;
+    if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3 && kv_dtype != MFA_KV_FP4_E2M1) return hipErrorNotSupported;
     if (a.q_len != 1 && !(a.q_len == 2 && a.n_wgs > 0)) return hipErrorNotSupported;   // two query tokens: balanced schedule only
     // The two events, when given, are attached to the streaming kernel's own dispatch: they take the
     // times at which that kernel starts and ends on the device, with no launch gap inside the interval.

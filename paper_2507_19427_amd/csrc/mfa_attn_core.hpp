@@ -109,19 +109,29 @@ __device__ __forceinline__ void load_q_fragments(bf16x8 (&qf)[8], const void* q,
 //               exactly (the 8 significant bits of bf16 are 4 + 4) down to 2^-9, i.e. to 2^-17 of the
 //               head's largest element.  A lane holds head n, d = 128*c + 32*g + j (j = 0..31, one
 //               byte each, in register order); inv_scale = 2^-e.
+//   4-bit cache: the same split; the keys enter the same MFMA as e2m1 operands (16 bytes per lane
+//               and 128 elements).  Measured on the device with one-hot operands: with an e2m1 A and
+//               an e4m3 B operand, element j of A's lane group g multiplies byte 16*(g >> 1) + (j & 15)
+//               of B's lane group 2*(g & 1) + (j >> 4).  The keys keep the plain order (a lane holds
+//               d = 128*c + 32*g + j, one 16-byte read), so the query takes the matching one: a lane
+//               holds d = 128*c + 64*(j >> 4) + 16*g + (j & 15).
 typedef int i32x8 __attribute__((ext_vector_type(8)));
-template <bool FP8> struct QFrags;
-template <> struct QFrags<false> { bf16x8 f[8]; };
-template <> struct QFrags<true> { i32x8 hi[2]; i32x8 lo[2]; float inv_scale; };
+struct SplitQuery { i32x8 hi[2]; i32x8 lo[2]; float inv_scale; };
+template <int BITS> struct QFrags;                    // BITS: width of a cache element (16, 8 or 4)
+template <> struct QFrags<16> { bf16x8 f[8]; };
+template <> struct QFrags<8> : SplitQuery {};
+template <> struct QFrags<4> : SplitQuery {};
 
-__device__ __forceinline__ void load_split_q_fp8(QFrags<true>& q, const void* qptr, int b, int head, int g)
+template <int BITS>
+__device__ __forceinline__ void load_split_q(QFrags<BITS>& q, const void* qptr, int b, int head, int g)
 {
-    const bf16x8* qp = (const bf16x8*)((const uint16_t*)qptr + ((size_t)b * kHeads + head) * kHeadDim + 32 * g);
+    static_assert(BITS == 8 || BITS == 4, "the split query serves the 8-bit and 4-bit caches");
+    const bf16x8* qp = (const bf16x8*)((const uint16_t*)qptr + ((size_t)b * kHeads + head) * kHeadDim + (BITS == 8 ? 32 : 16) * g);
     bf16x8 qf[2][4];
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) qf[c][i] = qp[c * 16 + i];
+        for (int i = 0; i < 4; ++i) qf[c][i] = qp[c * 16 + (BITS == 8 ? i : 8 * (i >> 1) + (i & 1))];
     float amax = 0.f;
 #pragma unroll
     for (int c = 0; c < 2; ++c)
@@ -162,9 +172,10 @@ __device__ __forceinline__ void load_split_q_fp8(QFrags<true>& q, const void* qp
 //   vbase      LDS byte offset of the unit's values: 32 rows of 512 B of bf16 (fp8: the codes
 //              converted, unscaled), 32-byte chunk c of row r stored at c ^ (r & 15)
 //   unit_t0    index (within the sequence) of the unit's first token; tokens >= t1 are masked
-//   FP8        kscale/vscale point (LDS byte offsets) at the fp32 per-token scales of the unit's 32 tokens
-template <bool FP8>
-__device__ __forceinline__ void process_unit(WaveState& st, const QFrags<FP8>& q, lds_ptr_t lds_base, int kbase,
+//                4 bit: 32 rows of 128 B of packed e2m1 codes, 16-byte chunk c of row r at c ^ ((r >> 1) & 7)
+//   8 / 4 bit  kscale/vscale point (LDS byte offsets) at the fp32 per-token scales of the unit's 32 tokens
+template <int BITS>
+__device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& q, lds_ptr_t lds_base, int kbase,
                                              int vbase, int unit_t0, int t1, float scale_log2e, int n, int g,
                                              int kscale_off, int vscale_off)
 {
@@ -172,8 +183,27 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<FP8>& q
     const int v_lane_off = v_row * 512 + ((n & 3) << 3);
 
     // ---- scores for 2 blocks of 16 tokens
+    constexpr bool FP8 = BITS != 16;                     // 8-bit arithmetic on the scores, scales beside the codes
     f32x4 s[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
-    if constexpr (FP8) {
+    if constexpr (BITS == 4) {
+        // e2m1 keys x e4m3 query terms with unit block scales (E8M0 exponent 127)
+        constexpr int kOne = 0x7F7F7F7F;
+        f32x4 slo[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const int row = kbase + tb * 2048 + n * 128;
+                const u32x4 k4 = *LDS_AT(u32x4, lds_base, row + (((4 * c + g) ^ ((n >> 1) & 7)) << 4));
+                const i32x8 kf = {(int)k4[0], (int)k4[1], (int)k4[2], (int)k4[3], 0, 0, 0, 0};
+                s[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf, q.hi[c], s[tb], 4, 0, 0, kOne, 0, kOne);
+                slo[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf, q.lo[c], slo[tb], 4, 0, 0, kOne, 0, kOne);
+            }
+        }
+        s[0] += slo[0];
+        s[1] += slo[1];
+        scale_log2e *= q.inv_scale;
+    } else if constexpr (BITS == 8) {
         // e4m3 x e4m3 with unit block scales (E8M0 exponent 127)
         constexpr int kOne = 0x7F7F7F7F;
         f32x4 slo[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};

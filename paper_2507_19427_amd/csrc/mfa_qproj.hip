@@ -283,14 +283,16 @@ __global__ __launch_bounds__(256) void rmsnorm_reduce_kernel(const float* __rest
 // quotient clamped to +-448; all in single precision with correctly rounded divisions, so that the
 // codes are a function of the fp32 row alone.  The row written is seq_lens[b] (the tokens already
 // cached); a row outside the cache or the block table is not written.
-template <bool FP8, bool PAGED>
+// 4-bit cache (BITS = 4): the same with e2m1's largest magnitude 6 in place of 448; the codes of
+// elements 2i and 2i + 1 share byte i, the even one in the low four bits.
+template <int BITS, bool PAGED>
 __global__ __launch_bounds__(kHeadDim) void kv_record_kernel(const float* __restrict__ parts, int split_k, int rows_pad,
                                                              KvAppendArgs a)
 {
     __shared__ float red[2][kHeadDim / 64];
     const int b = blockIdx.x;
     const int t = threadIdx.x;
-    float kx = 0.f, vx = 0.f;
+    float kx = -0.f, vx = -0.f;                         // -0 + x = x for every x, the sign of a zero included
     for (int z0 = 0; z0 < split_k; z0 += 8) {           // eight splits' loads in flight together, summed in split order
         float kp[8], vp[8];
 #pragma unroll
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(kHeadDim) void kv_record_kernel(const float* __rest
         if (pos < 0 || pos >= a.seq_stride_tokens) return;
         row = (int64_t)b * a.seq_stride_tokens + pos;
     }
-    if (!FP8) {
+    if (BITS == 16) {
         ((__bf16*)a.k)[row * kHeadDim + t] = (__bf16)kx;
         ((__bf16*)a.v)[row * kHeadDim + t] = (__bf16)vx;
         return;
@@ -328,12 +330,22 @@ __global__ __launch_bounds__(kHeadDim) void kv_record_kernel(const float* __rest
     __syncthreads();
     ka = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
     va = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
-    const float ks = fmaxf(ka, 1e-12f) / 448.0f;
-    const float vs = fmaxf(va, 1e-12f) / 448.0f;
-    const float ky = fminf(fmaxf(kx / ks, -448.0f), 448.0f);
-    const float vy = fminf(fmaxf(vx / vs, -448.0f), 448.0f);
-    ((uint8_t*)a.k)[row * kHeadDim + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(ky, 0.f, 0, false) & 0xFF);
-    ((uint8_t*)a.v)[row * kHeadDim + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(vy, 0.f, 0, false) & 0xFF);
+    constexpr float kTop = BITS == 8 ? 448.0f : 6.0f;
+    const float ks = fmaxf(ka, 1e-12f) / kTop;
+    const float vs = fmaxf(va, 1e-12f) / kTop;
+    const float ky = fminf(fmaxf(kx / ks, -kTop), kTop);
+    const float vy = fminf(fmaxf(vx / vs, -kTop), kTop);
+    if (BITS == 8) {
+        ((uint8_t*)a.k)[row * kHeadDim + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(ky, 0.f, 0, false) & 0xFF);
+        ((uint8_t*)a.v)[row * kHeadDim + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(vy, 0.f, 0, false) & 0xFF);
+    } else {
+        // the odd neighbour's quotient comes over by a lane shuffle; the even thread converts and stores the pair
+        const float ky1 = __shfl_down(ky, 1), vy1 = __shfl_down(vy, 1);
+        if ((t & 1) == 0) {
+            ((uint8_t*)a.k)[row * (kHeadDim / 2) + (t >> 1)] = (uint8_t)(__builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, ky, ky1, 1.0f, 0) & 0xFF);
+            ((uint8_t*)a.v)[row * (kHeadDim / 2) + (t >> 1)] = (uint8_t)(__builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, vy, vy1, 1.0f, 0) & 0xFF);
+        }
+    }
     if (t == 0) { a.k_scale[row] = ks; a.v_scale[row] = vs; }
 }
 static_assert(kHeadDim == 256, "kv_record_kernel reduces over four waves");
@@ -435,19 +447,26 @@ hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream)
 
 namespace {
 
-template <bool FP8>
-hipError_t launch_record(const KvAppendArgs& a, const float* parts, int split_k, int rows_pad, hipStream_t stream)
+template <int BITS>
+hipError_t launch_record_bits(const KvAppendArgs& a, const float* parts, int split_k, int rows_pad, hipStream_t stream)
 {
-    if (a.block_table) hipLaunchKernelGGL((kv_record_kernel<FP8, true>), dim3(a.B), dim3(kHeadDim), 0, stream, parts, split_k, rows_pad, a);
-    else               hipLaunchKernelGGL((kv_record_kernel<FP8, false>), dim3(a.B), dim3(kHeadDim), 0, stream, parts, split_k, rows_pad, a);
+    if (a.block_table) hipLaunchKernelGGL((kv_record_kernel<BITS, true>), dim3(a.B), dim3(kHeadDim), 0, stream, parts, split_k, rows_pad, a);
+    else               hipLaunchKernelGGL((kv_record_kernel<BITS, false>), dim3(a.B), dim3(kHeadDim), 0, stream, parts, split_k, rows_pad, a);
     return hipGetLastError();
+}
+
+hipError_t launch_record(const KvAppendArgs& a, mfa_kv_dtype kv_dtype, const float* parts, int split_k, int rows_pad, hipStream_t stream)
+{
+    if (kv_dtype == MFA_KV_FP8_E4M3) return launch_record_bits<8>(a, parts, split_k, rows_pad, stream);
+    if (kv_dtype == MFA_KV_FP4_E2M1) return launch_record_bits<4>(a, parts, split_k, rows_pad, stream);
+    return launch_record_bits<16>(a, parts, split_k, rows_pad, stream);
 }
 
 }  // namespace
 
 hipError_t launch_kv_record(const KvAppendArgs& a, const float* kv, mfa_kv_dtype kv_dtype, hipStream_t stream)
 {
-    return kv_dtype == MFA_KV_FP8_E4M3 ? launch_record<true>(a, kv, 1, a.B, stream) : launch_record<false>(a, kv, 1, a.B, stream);
+    return launch_record(a, kv_dtype, kv, 1, a.B, stream);
 }
 
 hipError_t launch_kv_append(const KvAppendArgs& a, mfa_kv_dtype kv_dtype, hipStream_t stream)
@@ -456,8 +475,7 @@ hipError_t launch_kv_append(const KvAppendArgs& a, mfa_kv_dtype kv_dtype, hipStr
     const int rows_pad = m_blocks * kQProjRows;
     const hipError_t e = launch_gemm<false, false>(a.x, a.w_kv, a.ws_c, a.B, a.d_model, kKvWidth, a.plan, a.plan.split_k, rows_pad, stream);
     if (e != hipSuccess) return e;
-    return kv_dtype == MFA_KV_FP8_E4M3 ? launch_record<true>(a, a.ws_c, a.plan.split_k, rows_pad, stream)
-                                       : launch_record<false>(a, a.ws_c, a.plan.split_k, rows_pad, stream);
+    return launch_record(a, kv_dtype, a.ws_c, a.plan.split_k, rows_pad, stream);
 }
 
 hipError_t launch_out_proj(const OutProjArgs& a, hipStream_t stream)

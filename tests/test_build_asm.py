@@ -1,4 +1,4 @@
-"""Host-side check of the compiled fp8 attention kernel.
+"""Host-side check of the compiled attention kernels for the 8-bit and 4-bit caches.
 
 Its register pipeline loads cache data with inline-assembly loads and waits for them with an
 inline-assembly s_waitcnt; between the two the compiler does not know that the destination registers are
@@ -46,7 +46,7 @@ def _regs(token):
     return {int(m.group(1))} if m else set()
 
 
-def _check_pipeline(lines):
+def _check_pipeline(lines, ops_per_step=5):
     in_asm = False
     queue = []                 # vector-memory operations in issue order: the registers each one writes
                                # (empty for direct-to-LDS loads, stores and compiler-made loads)
@@ -76,7 +76,7 @@ def _check_pipeline(lines):
             continue
         if op == "s_waitcnt" and "vmcnt" in rest:
             left = int(re.search(r"vmcnt\((\d+)\)", rest).group(1))
-            if in_asm and left == 5:
+            if in_asm and left == ops_per_step:
                 partial_waits += 1
             if not in_asm and partial_waits > 0:
                 # a compiler-made vector-memory wait inside the pipeline loop: it must not reach the
@@ -89,13 +89,15 @@ def _check_pipeline(lines):
             for o in operands[1:]:
                 sources |= _regs(o)
             assert not (sources & in_flight()), f"in-flight register copied before its wait: {t}"
-    assert partial_waits >= 2, "the two steps of the unrolled loop each wait with vmcnt(5)"
+    assert partial_waits >= 2, "the two steps of the unrolled loop each wait for all but the youngest step's loads"
 
 
+@pytest.mark.parametrize("bits,ops_per_step", [(8, 5), (4, 3)])
 @pytest.mark.parametrize("q_len", [1, 2])
 @pytest.mark.parametrize("paged", [0, 1])
-def test_fp8_pipeline_registers_stay_untouched_between_load_and_wait(asm_text, paged, q_len):
-    _check_pipeline(_kernel_body(asm_text, f"_ZN3mfa17decode_fp8_kernelILb{paged}ELi{q_len}EEEvNS_8AttnArgsE"))
+def test_lowbit_pipeline_registers_stay_untouched_between_load_and_wait(asm_text, paged, q_len, bits, ops_per_step):
+    name = f"_ZN3mfa20decode_lowbit_kernelILb{paged}ELi{q_len}ELi{bits}EEEvNS_8AttnArgsE"
+    _check_pipeline(_kernel_body(asm_text, name), ops_per_step)
 
 
 def _snippet(between):
