@@ -12,7 +12,7 @@ cache cannot serve it.
 --workload selects one of the other seeded workloads (ragged paged, long context, query path + fp8
 cache, the whole attention layer at the paper's 8K / 32K contexts); they exist so that kernel profiles of
 those shapes can be taken with this same program; cfg2q2 / fp8q2 run the step with two query tokens per
-sequence.
+sequence, fp4 / fp4q2 the 4-bit cache.
 
 Prints ONE JSON line: metric/value = KV tokens per second, plus
   roofline      HBM roofline of the streaming attention kernel from HIP-event timings taken in the timed region
@@ -120,10 +120,34 @@ def build_workload(key, mfa, W, n_sets):
         w.desc = ("configs[4]: B=128, query path 7168 -> 2048 -> RMSNorm -> 64x256, then attention over ctx 8192 of "
                   "fp8 e4m3 KV with per-token fp32 scales")
         w.metric = "KV tokens/s, MFA query path + decode attention, B=128, ctx 8192, fp8 KV, 1 GPU"
-        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16 (fp8 e4m3 KV storage)", "mfa::decode_fp8_kernel<false, 1>", 520
+        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16 (fp8 e4m3 KV storage)", "mfa::decode_lowbit_kernel<false, 1, 8>", 520
         w.T, w.B = case.kv_tokens, B
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S)}
         w.keep = [x, w_qa, w_qb]
+    elif key in ("fp4", "fp4q2"):
+        # 4-bit cache (Section 5.2: 4-bit storage, 8-bit arithmetic): the cache shape of configs[4] in e2m1
+        # codes, 264 bytes per token with the two fp32 scales.
+        case = W.make_contiguous_case(key, 6, B=128, S=8192, kv_dtype="fp4", poison=False)
+        B, S = case.B, case.k.shape[1]
+        q_len = 2 if key == "fp4q2" else 1
+        w.ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=S))
+        q = (W.make_multi_query(case, 2, 9) if q_len == 2 else case.q).cuda()
+        lens = case.seq_lens.cuda()
+        ks, vs = _roll_sets(case.k.cuda(), n_sets), _roll_sets(case.v.cuda(), n_sets)
+        kss, vss = _roll_sets(case.k_scale.cuda(), n_sets), _roll_sets(case.v_scale.cuda(), n_sets)
+        out = torch.empty(*q.shape, dtype=torch.float32, device="cuda")
+        w.steps = [mfa.PreparedDecodeAttn(w.ctx, q, ks[j], vs[j], lens, S, out, k_scale=kss[j], v_scale=vss[j])
+                   for j in range(n_sets)]
+        w.read_pairs = list(zip(ks, vs))
+        w.desc = ("B=%d, 64 q heads, 1 shared K/V head, head_dim 256, ctx %d, contiguous 4-bit e2m1 KV with per-token "
+                  "fp32 scales, %d query token(s) per sequence" % (B, S, q_len))
+        w.metric = "KV tokens/s, MFA decode attention%s, B=%d, ctx %d, fp4 KV, 1 GPU" % (
+            " with 2 query tokens" if q_len == 2 else "", B, S)
+        w.dtype = "bf16 (fp4 e2m1 KV storage, e4m3 score arithmetic)"
+        w.kernel = "mfa::decode_lowbit_kernel<false, %d, 4>" % q_len
+        w.kv_bytes_per_token = 264
+        w.T, w.B, w.q_len = case.kv_tokens, B, q_len
+        w.extra_config = {"query_tokens_per_sequence": q_len}
     elif key in ("cfg2q2", "fp8q2"):
         # Two new tokens per sequence in one pass over the cache (the multi-token step of Section 5.2):
         # same cache shapes as configs[1] / the cache of configs[4], twice the arithmetic per byte.
@@ -145,7 +169,7 @@ def build_workload(key, mfa, W, n_sets):
         w.metric = "KV tokens/s, MFA decode attention with 2 query tokens, B=%d, ctx %d, %s, 1 GPU" % (
             B, S, "fp8 KV" if fp8 else "bf16")
         w.dtype = "bf16 (fp8 e4m3 KV storage)" if fp8 else "bf16"
-        w.kernel = "mfa::decode_fp8_kernel<false, 2>" if fp8 else "mfa::decode_bf16_kernel<false, 2>"
+        w.kernel = "mfa::decode_lowbit_kernel<false, 2, 8>" if fp8 else "mfa::decode_bf16_kernel<false, 2>"
         w.kv_bytes_per_token = 520 if fp8 else 1024
         w.T, w.B, w.q_len = case.kv_tokens, B, 2
         w.extra_config = {"query_tokens_per_sequence": 2}
@@ -202,7 +226,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "cfg2q2", "fp8q2", "layer8k", "layer32k"), default="cfg2")
+    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "cfg2q2", "fp8q2", "fp4", "fp4q2", "layer8k", "layer32k"), default="cfg2")
     ap.add_argument("--buffer-sets", type=int, default=None, help="distinct KV buffer sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")

@@ -80,7 +80,7 @@ __device__ __forceinline__ float head_sum(float x)
 // Running state of one wave: 16 heads x 256 output dims, spread as described above.
 struct WaveState {
     f32x4 acc[16];
-    float m;     // running maximum of this head's scores in the log2 domain (equal in the 4 lanes of a head)
+    float m;     // reference exponent of the weights, log2 domain: within 8 below this head's running maximum (equal in the 4 lanes of a head)
     float l;     // this lane's share of the sum of weights
 };
 
@@ -264,9 +264,15 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& 
             m_raw = fmaxf(m_raw, sv[j]);
         }
     }
-    const float m_new = head_max(fmaxf(st.m, m_raw * scale_log2e));
+    // The reference exponent st.m follows the running maximum lazily: it moves only when the maximum
+    // has run ahead of it by more than kRescaleLag, so weights reach at most 2^kRescaleLag (harmless in
+    // bf16 and fp32) and the 64 accumulator registers are rescaled a few times per sequence instead of
+    // whenever some head of the wave sees a new maximum.  The normalisation at the end is unaffected.
+    constexpr float kRescaleLag = 8.0f;
+    const float m_seen = head_max(fmaxf(st.m, m_raw * scale_log2e));
+    const float m_new = m_seen > st.m + kRescaleLag ? m_seen : st.m;   // (-inf + lag = -inf: the first token always moves it)
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = fast_exp2(st.m - m_safe);      // 0 while nothing has been accumulated
+    const float alpha = fast_exp2(st.m - m_safe);      // 1 when unmoved; 0 while nothing has been accumulated
     st.m = m_new;
 
     bf16x8 pf;
