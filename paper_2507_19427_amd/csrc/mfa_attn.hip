@@ -82,22 +82,21 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
         auto issue_tile = [&](int tile, int slot, int page) {
             const int tile_t0 = r.t0 + tile * kTile;
             const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, page);
+            const unsigned char* k_tile = (const unsigned char*)a.k + row0 * 512;   // wave-uniform: scalar registers
+            const unsigned char* v_tile = (const unsigned char*)a.v + row0 * 512;
             const int p16 = lane & 31;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int row = 8 * wave + 2 * u + (lane >> 5);          // row of the tile this lane fills
                 int in_tile = row;
                 if (tile_t0 + row > r.t1 - 1) in_tile = r.t1 - 1 - tile_t0;
-                const size_t grow = (size_t)(row0 + in_tile) * 512;
                 const int key = row & 15;
                 const int ck = p16 ^ key;
                 const int cv = ((((p16 >> 1) ^ key) << 1) | (p16 & 1));
-                const unsigned char* ksrc = (const unsigned char*)a.k + grow + ck * 16;
-                const unsigned char* vsrc = (const unsigned char*)a.v + grow + cv * 16;
                 const int first_row = 8 * wave + 2 * u;                   // wave-uniform
                 const uint32_t dst = lds_addr0 + slot * kSlotBytes + (first_row >> 5) * kUnitBytes + (first_row & 31) * 512;
-                load_to_lds_16B(ksrc, dst);
-                load_to_lds_16B(vsrc, dst + kUnitVOffset);
+                load_to_lds_16B(k_tile, (uint32_t)(in_tile * 512 + ck * 16), dst);
+                load_to_lds_16B(v_tile, (uint32_t)(in_tile * 512 + cv * 16), dst + kUnitVOffset);
             }
         };
 
@@ -165,13 +164,14 @@ struct Fp8TileRegs {
 // vmcnt(0) at the loop's control-flow joins and drain the pipeline every tile.  The registers pass
 // through the waiting statement, so no use of them can be scheduled before it.
 template <int BITS> constexpr int kLowbitOpsPerStep = BITS == 8 ? 5 : 3;
-__device__ __forceinline__ void load_regs_16B(u32x4& dst, const void* p)
+// (address = wave-uniform base in scalar registers + 32-bit byte offset per lane)
+__device__ __forceinline__ void load_regs_16B(u32x4& dst, const void* sbase, uint32_t voff)
 {
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(dst) : "v"(voff), "s"(sbase) : "memory");
 }
-__device__ __forceinline__ void load_regs_4B(float& dst, const void* p)
+__device__ __forceinline__ void load_regs_4B(float& dst, const void* sbase, uint32_t voff)
 {
-    asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
+    asm volatile("global_load_dword %0, %1, %2" : "=&v"(dst) : "v"(voff), "s"(sbase) : "memory");
 }
 template <int BITS>
 __device__ __forceinline__ void wait_all_but_youngest_step(Fp8TileRegs& t)
@@ -237,11 +237,11 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
             for (int i = 0; i < (BITS == 8 ? 2 : 1); ++i) {
                 const int row = prow + 32 * i;
                 const int in_tile = row > last ? last : row;
-                load_regs_16B(t.piece[i], (const unsigned char*)a.v + (size_t)(row0 + in_tile) * kRowBytes + pchunk * 16);
+                load_regs_16B(t.piece[i], (const unsigned char*)a.v + row0 * kRowBytes, (uint32_t)(in_tile * kRowBytes + pchunk * 16));
             }
-            const int tok = threadIdx.x & 63;                              // threads 128.. repeat those of 0..127
+            const int tok = lane;                                          // waves 2.. repeat those of waves 0 and 1
             const int in_tile = tok > last ? last : tok;
-            load_regs_4B(t.scale, ((threadIdx.x & 64) ? a.v_scale : a.k_scale) + (row0 + in_tile));
+            load_regs_4B(t.scale, ((wave & 1) ? a.v_scale : a.k_scale) + row0, (uint32_t)(in_tile * 4));
         };
         // Keys of a tile.  8 bit: 16 direct loads of 4 rows, wave w issues loads 2w and 2w + 1, 16-byte
         // chunk c of row r lands at c ^ (r & 15).  4 bit: 8 direct loads of 8 rows, one per wave, chunk c
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                     const int row = first_row + (lane >> 4);
                     const int in_tile = row > last ? last : row;
                     const int c16 = (lane & 15) ^ (row & 15);
-                    load_to_lds_16B((const unsigned char*)a.k + (size_t)(row0 + in_tile) * 256 + c16 * 16,
+                    load_to_lds_16B((const unsigned char*)a.k + row0 * 256, (uint32_t)(in_tile * 256 + c16 * 16),
                                     lds_addr0 + kFp8KBase + kslot * kFp8KSlotBytes + first_row * 256);
                 }
             } else {
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                 const int row = first_row + (lane >> 3);
                 const int in_tile = row > last ? last : row;
                 const int c16 = (lane & 7) ^ ((row >> 1) & 7);
-                load_to_lds_16B((const unsigned char*)a.k + (size_t)(row0 + in_tile) * 128 + c16 * 16,
+                load_to_lds_16B((const unsigned char*)a.k + row0 * 128, (uint32_t)(in_tile * 128 + c16 * 16),
                                 lds_addr0 + kFp8KBase + kslot * kFp8KSlotBytes + first_row * 128);
             }
         };
@@ -277,12 +277,13 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                     bf16x8 half[2];
 #pragma unroll
                     for (int w = 0; w < 4; ++w) {
-                        const auto f01 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], false);
-                        const auto f23 = __builtin_amdgcn_cvt_pk_f32_fp8(t.piece[i][w], true);
-                        half[w >> 1][4 * (w & 1) + 0] = (__bf16)f01[0];
-                        half[w >> 1][4 * (w & 1) + 1] = (__bf16)f01[1];
-                        half[w >> 1][4 * (w & 1) + 2] = (__bf16)f23[0];
-                        half[w >> 1][4 * (w & 1) + 3] = (__bf16)f23[1];
+                        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                        const bf16x2 p01 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(t.piece[i][w], 1.0f, false);
+                        const bf16x2 p23 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(t.piece[i][w], 1.0f, true);
+                        half[w >> 1][4 * (w & 1) + 0] = p01[0];
+                        half[w >> 1][4 * (w & 1) + 1] = p01[1];
+                        half[w >> 1][4 * (w & 1) + 2] = p23[0];
+                        half[w >> 1][4 * (w & 1) + 3] = p23[1];
                     }
                     const int key = prow & 15;                                 // row within its unit = prow (0..31)
                     const int off = image * kFp8VImageBytes + i * 16384 + prow * 512 + ((pchunk ^ key) << 5);

@@ -49,6 +49,13 @@ __device__ __forceinline__ void load_to_lds_16B(const void* gptr, uint32_t lds_a
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :: "v"(gptr), "s"(lds_addr) : "memory");
 }
+// The same with the address given as a wave-uniform base (scalar registers) plus a 32-bit byte
+// offset per lane: no 64-bit vector arithmetic per load.
+__device__ __forceinline__ void load_to_lds_16B(const void* sbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
 __device__ __forceinline__ void load_to_lds_4B(const void* gptr, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
