@@ -30,8 +30,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published peak
 # HBM bytes per launch of the streaming kernel on the default workload, from rocprofv3 --pmc FETCH_SIZE
 # and WRITE_SIZE scaled by what the same counters read for a 256 MiB device copy
-# (profiles/decode_attn_cfg2_b64_ctx4096_hbm_traffic.md): 277.08 MB read + 16.91 MB written.
-MEASURED_TRAFFIC_BYTES = {"cfg2": 135295 * 2.000 * 1024 + 16513 * 1.000 * 1024}
+# (profiles/decode_attn_cfg2_b64_ctx4096_hbm_traffic.md): 277.07 MB read + 16.91 MB written.
+MEASURED_TRAFFIC_BYTES = {"cfg2": 135287 * 2.000 * 1024 + 16513 * 1.000 * 1024,
+                          # profiles/decode_attn_other_workloads_hbm_traffic.md
+                          "cfg4": 264310 * 2.000 * 1024 + 16512 * 1024, "cfg5": 270502 * 2.000 * 1024 + 16516 * 1024,
+                          "fp4": 139425 * 2.000 * 1024 + 16516 * 1024, "cfg2q2": 139380 * 2.000 * 1024 + 33025 * 1024}
 Q_BYTES_PER_SEQ = 64 * 256 * 2
 OUT_BYTES_PER_SEQ = 64 * 256 * 4
 STREAM_READ_GRANULE = 2048 * 8192      # the plain-read probe takes multiples of this many bytes per buffer
