@@ -239,8 +239,10 @@ MFA_API mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_
  * (seq_lens[b] < q_len) gets the zero row.
  *   q    bf16 [B, q_len, n_q_heads, head_dim]
  *   out  fp32 [B, q_len, n_q_heads, head_dim]     (written)
- * q_len = 1 is mfa_decode_attn[_paged]; q_len = 2 is built (balanced work distribution only, i.e.
- * B <= 4096); larger q_len returns MFA_ERR_UNSUPPORTED.  Everything else as for q_len = 1.
+ * 1 <= q_len <= 4 (larger: MFA_ERR_UNSUPPORTED); q_len = 1 is mfa_decode_attn[_paged].  Two query
+ * tokens share one pass over the cache; three and four are worked off as two such pairs, i.e. two
+ * passes.  Several query tokens need the balanced work distribution (B <= 4096, no MFA_SCHEDULE=fixed).
+ * Everything else as for q_len = 1.
  */
 MFA_API mfa_status mfa_decode_attn_multi(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
                                  const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,

@@ -135,6 +135,7 @@ void fill_common(const mfa_ctx* ctx, AttnArgs& a, int32_t B, int32_t hint)
     a.chunk_tokens = p.chunk_tokens;
     a.B = B;
     a.q_len = 1;
+    a.q0 = 0;
     a.max_seq_len_hint = hint;
     a.ws_acc = ctx->ws_acc;
     a.ws_ml = ctx->ws_ml;
@@ -351,7 +352,7 @@ mfa_status mfa_decode_attn_multi(mfa_ctx* ctx, const void* q, const void* k_cach
     if (st != MFA_OK) return st;
     if (kv_seq_stride_tokens < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
     if (q_len < 1) return MFA_ERR_INVALID_ARG;
-    if (q_len > 2) return MFA_ERR_UNSUPPORTED;
+    if (q_len > kMaxQueryTokens) return MFA_ERR_UNSUPPORTED;
     AttnArgs a{};
     a.q = q; a.k = k_cache; a.v = v_cache; a.k_scale = k_scale; a.v_scale = v_scale;
     a.seq_lens = seq_lens; a.block_table = nullptr; a.out = out;
@@ -384,7 +385,7 @@ mfa_status mfa_decode_attn_paged_multi(mfa_ctx* ctx, const void* q, const void* 
     if (!block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u) || n_pages < 1) return MFA_ERR_INVALID_ARG;
     if ((int64_t)max_blocks_per_seq * kPage < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
     if (q_len < 1) return MFA_ERR_INVALID_ARG;
-    if (q_len > 2) return MFA_ERR_UNSUPPORTED;
+    if (q_len > kMaxQueryTokens) return MFA_ERR_UNSUPPORTED;
     AttnArgs a{};
     a.q = q; a.k = k_pool; a.v = v_pool; a.k_scale = k_scale_pool; a.v_scale = v_scale_pool;
     a.seq_lens = seq_lens; a.block_table = block_table; a.out = out;

@@ -49,8 +49,9 @@ __device__ __forceinline__ int64_t tile_row0(const AttnArgs& a, int b, int tile_
 }
 
 // QL = query tokens per sequence.  1: wave = 4*(token half of the tile) + head group.  2: wave =
-// 4*(query token) + head group, and every wave works through both halves of each tile; query token j
-// attends to the first len - (QL - 1 - j) cached tokens (the new tokens are the last QL of the cache).
+// 4*(query token of the pair q0, q0 + 1) + head group, and every wave works through both halves of each
+// tile; query token j of q_len attends to the first len - (q_len - 1 - j) cached tokens (the new tokens are
+// the last q_len of the cache).  More than two query tokens are worked off pair by pair, one launch each.
 template <bool PAGED, int QL>
 __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
 {
@@ -73,8 +74,9 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
         first_segment = false;
 
         QFrags<16> q;
-        load_q_fragments(q.f, a.q, QL == 2 ? 2 * r.b + grp : r.b, 16 * wq + n, g);
-        const int t1_mine = QL == 2 ? (r.t1 < r.len - 1 + grp ? r.t1 : r.len - 1 + grp) : r.t1;   // grp = query token when QL == 2
+        load_q_fragments(q.f, a.q, QL == 2 ? a.q_len * r.b + a.q0 + grp : r.b, 16 * wq + n, g);
+        const int end_mine = r.len - (a.q_len - 1 - a.q0 - grp);      // QL == 2: grp = query token of the pair
+        const int t1_mine = QL == 2 ? (r.t1 < end_mine ? r.t1 : end_mine) : r.t1;
 
         // Wave w brings rows [8w, 8w+8) of the tile's K and V: all in unit w/4.  Rows at or past t1
         // re-read the last valid token, so nothing outside the sequence is touched and every LDS row
@@ -322,8 +324,9 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
         // The query fragments are loaded by ordinary loads: the compiler completes them, and with them
         // everything above, right here instead of inside the loop.
         QFrags<BITS> q;
-        load_split_q<BITS>(q, a.q, QL == 2 ? 2 * r.b + grp : r.b, 16 * wq + n, g);
-        const int t1_mine = QL == 2 ? (r.t1 < r.len - 1 + grp ? r.t1 : r.len - 1 + grp) : r.t1;   // grp = query token when QL == 2
+        load_split_q<BITS>(q, a.q, QL == 2 ? a.q_len * r.b + a.q0 + grp : r.b, 16 * wq + n, g);
+        const int end_mine = r.len - (a.q_len - 1 - a.q0 - grp);      // QL == 2: grp = query token of the pair
+        const int t1_mine = QL == 2 ? (r.t1 < end_mine ? r.t1 : end_mine) : r.t1;
         asm volatile("" : "+v"(q.hi[0]), "+v"(q.hi[1]), "+v"(q.lo[0]), "+v"(q.lo[1]));
         drain_tiles<BITS>(regs[0], regs[1]);
         store_tile(regs[0], 0);
@@ -366,12 +369,13 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
 // taken four at a time so that their loads are independent and in flight together.
 __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B * q_len * 4096 float4
+    const int n_here = a.q_len == 1 ? 1 : 2;                          // query tokens of this launch
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B * n_here * 4096 float4
     const int p = (int)(idx & 4095);                                  // position in the partial's lane-order layout
-    const int bq = (int)(idx >> 12);                                  // sequence * q_len + query token
-    if (bq >= a.B * a.q_len) return;
-    const int b = bq / a.q_len;
-    const int qtok = bq - b * a.q_len;
+    const int bq = (int)(idx >> 12);                                  // sequence * n_here + query token of the launch
+    if (bq >= a.B * n_here) return;
+    const int b = bq / n_here;
+    const int qtok = bq - b * n_here;
     const int lane = p & 63;
     const int db = (p >> 6) & 15;
     const int wq = p >> 10;
@@ -379,8 +383,8 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
     const int d = 16 * db + 4 * (lane >> 4);
     int L = a.seq_lens[b];
     L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
-    float4* const o = (float4*)(a.out + ((size_t)bq * kHeads + h) * kHeadDim + d);
-    const int L_mine = L - (a.q_len - 1 - qtok);                      // tokens this query token attends to
+    float4* const o = (float4*)(a.out + (((size_t)b * a.q_len + a.q0 + qtok) * kHeads + h) * kHeadDim + d);
+    const int L_mine = L - (a.q_len - 1 - a.q0 - qtok);               // tokens this query token attends to
     int n_valid;
     size_t item0;
     if (a.n_wgs > 0) {                                                // balanced schedule
@@ -393,9 +397,9 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
         n_valid = (L + a.chunk_tokens - 1) / a.chunk_tokens;          // <= n_splits
         item0 = (size_t)b * a.n_splits;
     }
-    if (L_mine <= 0) { *o = make_float4(0.f, 0.f, 0.f, 0.f); return; }   // (only with two query tokens and L = 1)
-    const size_t slot0 = item0 * a.q_len + qtok;                      // partial of (item, query token) at item*q_len + qtok
-    const size_t slot_step = (size_t)a.q_len;
+    if (L_mine <= 0) { *o = make_float4(0.f, 0.f, 0.f, 0.f); return; }   // (only with several query tokens and L < q_len)
+    const size_t slot0 = item0 * n_here + qtok;                       // partial of (item, query token) at item*n_here + qtok
+    const size_t slot_step = (size_t)n_here;
     const float2* ml_base = (const float2*)a.ws_ml + slot0 * kHeads + h;
     const float4* acc_base = (const float4*)a.ws_acc + slot0 * (kHeads * kHeadDim / 4) + p;
 
@@ -527,24 +531,35 @@ hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStrea
     const dim3 grid((unsigned)(a.n_wgs > 0 ? a.n_wgs : a.B * a.n_splits));
     const dim3 block(kAttnThreads);
     if (kv_dtype != MFA_KV_BF16 && kv_dtype != MFA_KV_FP8_E4M3 && kv_dtype != MFA_KV_FP4_E2M1) return hipErrorNotSupported;
-    if (a.q_len != 1 && !(a.q_len == 2 && a.n_wgs > 0)) return hipErrorNotSupported;   // two query tokens: balanced schedule only
+    if (a.q_len < 1 || a.q_len > kMaxQueryTokens) return hipErrorNotSupported;
+    if (a.q_len != 1 && a.n_wgs == 0) return hipErrorNotSupported;     // several query tokens: balanced schedule only
     // The two events, when given, are attached to the streaming kernel's own dispatch: they take the
     // times at which that kernel starts and ends on the device, with no launch gap inside the interval.
+    // (With more than two query tokens: the first pair's.)
     if (!(ev_before && ev_after)) ev_before = ev_after = nullptr;
     const unsigned lds_bytes = a.n_wgs > 0 ? kAttnLdsTotal : kSchedLdsOffset;   // the schedule's arrays only if used
-    const void* kernel = a.q_len == 2 ? attn_kernel<2>(kv_dtype, a.block_table != nullptr) : attn_kernel<1>(kv_dtype, a.block_table != nullptr);
-    AttnArgs args = a;
-    void* params[] = {&args};
-    hipError_t e = hipExtLaunchKernel(kernel, grid, block, params, lds_bytes, stream, ev_before, ev_after, 0);
-    if (e != hipSuccess) return e;
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (a.n_wgs > 0 || a.n_splits > 1) {
-        const unsigned blocks = (unsigned)(((size_t)a.B * a.q_len * kHeads * (kHeadDim / 4) + 255) / 256);
-        hipLaunchKernelGGL(merge_splits_kernel, dim3(blocks), dim3(256), 0, stream, a);
+    const void* kernel = a.q_len >= 2 ? attn_kernel<2>(kv_dtype, a.block_table != nullptr) : attn_kernel<1>(kv_dtype, a.block_table != nullptr);
+    const int n_here = a.q_len == 1 ? 1 : 2;
+    // Query tokens are worked off in pairs (q0, q0 + 1), one pass over the cache each; an odd count ends
+    // with the pair (q_len - 2, q_len - 1), which computes token q_len - 2 a second time with the same result.
+    // The passes share the partial-result workspace: they are ordered by the stream.
+    for (int q0 = 0; q0 < a.q_len; q0 += 2) {
+        AttnArgs args = a;
+        args.q0 = q0 + n_here <= a.q_len ? q0 : a.q_len - n_here;
+        void* params[] = {&args};
+        hipError_t e = hipExtLaunchKernel(kernel, grid, block, params, lds_bytes, stream, q0 == 0 ? ev_before : nullptr,
+                                          q0 == 0 ? ev_after : nullptr, 0);
+        if (e != hipSuccess) return e;
         e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (a.n_wgs > 0 || a.n_splits > 1) {
+            const unsigned blocks = (unsigned)(((size_t)a.B * n_here * kHeads * (kHeadDim / 4) + 255) / 256);
+            hipLaunchKernelGGL(merge_splits_kernel, dim3(blocks), dim3(256), 0, stream, args);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
     }
-    return e;
+    return hipSuccess;
 }
 
 hipError_t launch_gather_paged(const void* pool, int32_t row_bytes, const int32_t* block_table,

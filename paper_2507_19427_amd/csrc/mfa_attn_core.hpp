@@ -405,7 +405,7 @@ __device__ __forceinline__ void finish_segment_two(WaveState& st, const AttnArgs
     const int n = lane & 15, g = lane >> 4;
     const int head = 16 * wq + n;
     const float l = head_sum(st.l);
-    const size_t row = (size_t)r.b * 2 + qtok;
+    const size_t row = (size_t)r.b * a.q_len + a.q0 + qtok;
     if (r.final_result) {
         const float inv = l > 0.f ? 1.0f / l : 0.f;
         float* o = a.out + (row * kHeads + head) * kHeadDim + 4 * g;

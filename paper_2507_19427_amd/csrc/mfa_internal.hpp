@@ -28,6 +28,7 @@ SplitPlan plan_splits(int32_t B, int32_t max_seq_len_hint, int32_t target_items)
 // laid end to end in sequence order, are cut into n_wgs equal ranges, one per workgroup; a range
 // that crosses sequence boundaries is worked off as one segment per sequence.  The workgroup
 // count, and the number of partial-result slots that any schedule over it can need.
+constexpr int32_t kMaxQueryTokens = 4;         // query tokens per sequence and call
 constexpr int32_t kMaxBalancedBatch = 4096;
 int32_t balanced_workgroups(int32_t B, int32_t max_seq_len_hint, int32_t target_items);   // 0 if B is too large
 inline size_t balanced_slots(int32_t B, int32_t n_wgs) { return (size_t)B + (size_t)n_wgs; }
@@ -52,7 +53,9 @@ struct AttnArgs {
     int64_t seq_stride_tokens;     // contiguous only
     int32_t max_blocks_per_seq;    // paged only
     int32_t B;
-    int32_t q_len;                 // query tokens per sequence: 1, or 2 (q, out, partial slots are then [.., 2, ..])
+    int32_t q_len;                 // query tokens per sequence (q and out are [B, q_len, 64, 256])
+    int32_t q0;                    // first query token this launch works on: a launch takes token q0 (q_len == 1)
+                                   // or the pair q0, q0 + 1; partial slots of a pair are [.., 2, ..]
     int32_t n_wgs;                 // > 0: balanced schedule over this many workgroups; 0: fixed splits below
     int32_t n_splits;
     int32_t chunk_tokens;

@@ -44,8 +44,8 @@ def _oracle(case, qm, rows=None):
     return np.stack(outs, axis=1)
 
 
-def _check(case, ctx, tol, hint=None, q_seed=900):
-    qm = W.make_multi_query(case, 2, q_seed)
+def _check(case, ctx, tol, hint=None, q_seed=900, q_len=2):
+    qm = W.make_multi_query(case, q_len, q_seed)
     got = _run_gpu(ctx, case, qm, hint=hint)
     ref = _oracle(case, qm)
     err = U.row_normalised_error(got, ref)
@@ -54,8 +54,9 @@ def _check(case, ctx, tol, hint=None, q_seed=900):
     for b, L in enumerate(case.seq_lens.tolist()):
         if L == 0:
             assert (got[b] == 0).all()
-        if L == 1:
-            assert (got[b, 0] == 0).all()          # the first new token has nothing before it
+        for j in range(q_len):
+            if L < q_len - j:
+                assert (got[b, j] == 0).all()      # this new token has nothing to attend to
     return got, qm
 
 
@@ -130,10 +131,32 @@ def test_one_token_through_the_multi_entry_point_is_the_single_token_path():
     assert np.array_equal(a, b[:, 0])
 
 
+@pytest.mark.parametrize("q_len", [3, 4])
+@pytest.mark.parametrize("kv_dtype,tol", [("bf16", U.TOL_BF16), ("fp8", U.TOL_FP8)])
+def test_three_and_four_tokens_in_pairs(q_len, kv_dtype, tol):
+    """More than two query tokens are worked off pair by pair; an odd count ends with an overlapping pair."""
+    _announce(f"{q_len} query tokens, {kv_dtype}")
+    lens = [0, 1, 2, 3, 4, 64, 65, 66, 67, 129, 1500, 700]
+    case = W.make_contiguous_case("mtp34", 780 + q_len, B=len(lens), S=1504, seq_lens=lens, kv_dtype=kv_dtype, poison=True)
+    _check(case, U.get_ctx(), tol, q_len=q_len)
+
+
+def test_four_tokens_paged_bitwise_equal_to_contiguous():
+    _announce("4 query tokens, paged vs contiguous")
+    g = torch.Generator().manual_seed(791)
+    lens = torch.randint(1, 401, (40,), generator=g).tolist()
+    lens[2], lens[7], lens[9] = 0, 2, 3
+    case = W.make_paged_case("mtp4paged", 792, lens, spare_pages=5, poison=True)
+    contig = W.paged_to_contiguous(case, S=448, poison=True)
+    ctx = U.get_ctx()
+    got_p, qm = _check(case, ctx, U.TOL_BF16, hint=400, q_len=4)
+    assert np.array_equal(got_p, _run_gpu(ctx, contig, qm, hint=400))
+
+
 def test_unsupported_query_counts_are_refused(monkeypatch):
-    _announce("q_len=3 and q_len=2 on fixed splits are refused")
+    _announce("q_len=5 and q_len=2 on fixed splits are refused")
     case = W.make_contiguous_case("mtpbad", 761, B=2, S=64, seq_lens=[64, 10], poison=True)
-    q3 = W.make_multi_query(case, 3, 762)
+    q3 = W.make_multi_query(case, 5, 762)
     with pytest.raises(mfa.MfaError) as ei:
         _run_gpu(U.get_ctx(), case, q3)
     assert ei.value.status == mfa.MFA_ERR_UNSUPPORTED
