@@ -73,3 +73,41 @@ def step3_attention_cost_per_million_tokens(ctx, cost_per_flop, cost_per_byte, l
         cost_per_flop, cost_per_byte)
     return 1e6 * per_token
 
+
+
+# ---------------------------------------------------------------------------
+# Roofline of an accelerator as the paper uses the word (Section 5.1): peak
+# computation over peak memory bandwidth, in flop per byte.  An attention design
+# whose arithmetic intensity is below it is bound by memory, above it by compute.
+# ---------------------------------------------------------------------------
+
+def ridge_point(peak_flops, peak_bytes_per_s):
+    return peak_flops / peak_bytes_per_s
+
+
+def ridge_point_from_unit_costs(cost_per_flop, cost_per_byte):
+    """The same ratio from the paper's unit-cost table: the hourly price cancels."""
+    return cost_per_byte / cost_per_flop
+
+
+def attention_time_bound(kv_tokens, bytes_per_kv_token, flops_per_kv_token, peak_flops, peak_bytes_per_s):
+    """Lower bound (seconds) on one attention call that reads kv_tokens cached tokens: the larger of
+    its memory time and its compute time at the accelerator's peaks."""
+    return max(kv_tokens * bytes_per_kv_token / peak_bytes_per_s, kv_tokens * flops_per_kv_token / peak_flops)
+
+
+# The accelerator this build runs on, by its published dense peaks (no price is asserted, so no cost
+# column follows from it): the extension of the paper's accelerator table by one column.
+MI355X = {"peak_flops_bf16": 2.5e15, "peak_flops_8bit": 5.0e15, "peak_bytes_per_s": 8.0e12}
+
+
+def mi355x_column(n_q_heads=64, head_dim=256):
+    """Where MFA's arithmetic intensity sits against MI355X, for the cache widths and query-token
+    counts this build supports: {(bytes per element, query tokens): (intensity, ridge, bound)}."""
+    out = {}
+    for bytes_per_elem, peak in ((2, MI355X["peak_flops_bf16"]), (1, MI355X["peak_flops_8bit"]), (0.5, MI355X["peak_flops_8bit"])):
+        ridge = ridge_point(peak, MI355X["peak_bytes_per_s"])
+        for q_tokens in (1, 2, 4):
+            ai = q_tokens * arithmetic_intensity(n_q_heads, head_dim, bytes_per_elem)
+            out[(bytes_per_elem, q_tokens)] = (ai, ridge, "memory" if ai < ridge else "compute")
+    return out

@@ -73,3 +73,30 @@ def test_cost_formula_takes_the_larger_of_compute_and_memory():
     assert abs(bad_sum - g["attn_cost_8k_H20"]) > 0.005
     cf, cb = pc.unit_costs(3600.0, 1e15, 1e12)
     assert cf == 1e-15 and cb == 1e-12
+
+
+def test_printed_rooflines_follow_from_the_printed_unit_costs():
+    """Section 5.1 quotes the computation-bandwidth ratio of three accelerators; Section 4.2's unit costs give
+    the same ratios (the hourly price cancels).  Two places of the paper that must agree, and do."""
+    g = _golden()
+    for hw in ("H20", "A800", "910B"):
+        ratio = pc.ridge_point_from_unit_costs(g["unit_cost_flop_" + hw], g["unit_cost_byte_" + hw])
+        assert abs(ratio - g["roofline_" + hw]) <= 0.01 * g["roofline_" + hw], (hw, ratio)
+    cf, cb = pc.unit_costs(2.0, 1e15, 2e12)
+    assert abs(pc.ridge_point_from_unit_costs(cf, cb) - pc.ridge_point(1e15, 2e12)) < 1e-9 * 500
+    # MFA at 8 bits (128) sits below A800 and 910B and above H20, as the text says
+    ai = pc.arithmetic_intensity(int(g["n_q_heads"]), int(g["head_dim"]), 1)
+    assert g["roofline_H20"] < ai < g["roofline_A800"] < g["roofline_910B"]
+
+
+def test_mi355x_column():
+    """The extension by this build's accelerator: by the paper's own model MFA stays on the memory side of
+    MI355X's ridge for every cache width and query-token count built here except 4-bit with four tokens."""
+    col = pc.mi355x_column()
+    assert col[(2, 1)][:2] == (64.0, 312.5) and col[(1, 1)][:2] == (128.0, 625.0) and col[(0.5, 1)][:2] == (256.0, 625.0)
+    assert col[(1, 2)][0] == 256.0 and col[(0.5, 2)][0] == 512.0
+    assert all(bound == "memory" for (w, n), (_, _, bound) in col.items() if (w, n) != (0.5, 4))
+    assert col[(0.5, 4)][2] == "compute"
+    # lower bound of the benchmark call: 64 x 4096 tokens, 1024 bytes and 4*64*256 flop per cached token
+    t = pc.attention_time_bound(64 * 4096, 1024, 4 * 64 * 256, pc.MI355X["peak_flops_bf16"], pc.MI355X["peak_bytes_per_s"])
+    assert abs(t - 33.554432e-6) < 1e-12
