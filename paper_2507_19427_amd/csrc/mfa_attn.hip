@@ -1,25 +1,26 @@
 // Decode-step MFA attention for gfx950: 64 query heads of dimension 256 over one
 // shared key head and one shared value head (paper, Section 2), one query token
-// per sequence, independent sequences (Section 7.1).
+// per sequence (or a pair, Section 5.2), independent sequences (Section 7.1).
 //
-// Work decomposition.  A work item is (sequence b, context split s): it streams
-// the tokens [s*chunk, min(L_b, (s+1)*chunk)) once from HBM.  With one split it
-// writes the final output; otherwise it leaves an unnormalised partial
-// (acc, m, l) in the workspace that merge_splits_kernel reduces in split order.
-// One workgroup of 8 waves per work item; mfa_attn_core.hpp describes how the
-// waves share a tile and the MFMA operand layouts.
+// Work decomposition.  A workgroup of 8 waves works off segments: pieces
+// [t0, t1) of one sequence's tokens, streamed once from HBM (mfa_attn_core.hpp:
+// which segments a workgroup gets, how the waves share a tile, the MFMA operand
+// layouts).  A segment that covers its whole sequence writes the final output;
+// otherwise it leaves an unnormalised partial (acc, m, l) in the workspace that
+// merge_splits_kernel reduces in order of position.
 //
 // bf16 cache: tiles of 64 tokens (= one cache page) are brought in with 16-byte
 // global->LDS direct loads into a two-slot ring (64 KB per slot: two 32-token
 // unit images).  The XOR swizzle of the unit image is applied on the global side
 // of the direct load because its LDS side is fixed to base + 16*lane.
 //
-// fp8 cache (OCP e4m3, one fp32 scale per token per tensor): the codes of a tile
-// travel through registers (plain coalesced 16-byte loads, two tiles ahead), the
-// whole workgroup converts them once to bf16 (exact) into one of two bf16 tile
-// images in LDS, and the same MFMA path runs on the image.  The key scale
-// multiplies the score column of its token, the value scale rides on the
-// attention weight of its token.
+// 8-bit and 4-bit caches (e4m3 / e2m1 codes, one fp32 scale per token per
+// tensor): the key codes go by direct loads into a three-slot ring and are
+// multiplied as they are on the 8-bit MFMA against a two-term e4m3 query; the
+// value codes travel through registers two tiles ahead and are expanded to bf16
+// (exactly) into one of two value images for the same weighted-sum path as bf16.
+// The key scale multiplies the score column of its token, the value scale rides
+// on the attention weight of its token.
 #include <hip/hip_ext.h>
 #include <type_traits>
 
@@ -145,16 +146,16 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
 // LDS: value image P (P = tile & 1) at P*32 KB, its unit g at + g*16 KB; key slot k (tile % 3) at
 // 64 KB + k*16 KB (4 bit: the first 8 KB of it); scale set P at 112 KB + P*512 B (64 key scales, then
 // 64 value scales).
-constexpr int kFp8VImageBytes = 2 * 16384;
-constexpr int kFp8KBase = 2 * kFp8VImageBytes;
-constexpr int kFp8KSlotBytes = kTile * 256;
-constexpr int kFp8KSlots = 3;
-constexpr int kFp8ScaleBase = kFp8KBase + kFp8KSlots * kFp8KSlotBytes;
-constexpr int kFp8LdsBytes = kFp8ScaleBase + 2 * 512;
-static_assert(kFp8LdsBytes <= kSchedLdsOffset && kAttnLdsBytes <= kSchedLdsOffset && kAttnLdsTotal <= 160 * 1024,
+constexpr int kLbVImageBytes = 2 * 16384;
+constexpr int kLbKBase = 2 * kLbVImageBytes;
+constexpr int kLbKSlotBytes = kTile * 256;
+constexpr int kLbKSlots = 3;
+constexpr int kLbScaleBase = kLbKBase + kLbKSlots * kLbKSlotBytes;
+constexpr int kLbLdsBytes = kLbScaleBase + 2 * 512;
+static_assert(kLbLdsBytes <= kSchedLdsOffset && kAttnLdsBytes <= kSchedLdsOffset && kAttnLdsTotal <= 160 * 1024,
               "the schedule's prefix sums live behind the tile memory of both kernels");
 
-struct Fp8TileRegs {
+struct LowbitTileRegs {
     u32x4 piece[2];       // 8 bit: V rows prow and prow + 32, 16-byte chunk pchunk; 4 bit: piece[0] only,
                           // V row tid / 8, 16-byte chunk tid % 8 (32 elements)
     float scale;          // threads 0..63: key scale of token tid; 64..127: value scale of token tid - 64
@@ -176,7 +177,7 @@ __device__ __forceinline__ void load_regs_4B(float& dst, const void* sbase, uint
     asm volatile("global_load_dword %0, %1, %2" : "=&v"(dst) : "v"(voff), "s"(sbase) : "memory");
 }
 template <int BITS>
-__device__ __forceinline__ void wait_all_but_youngest_step(Fp8TileRegs& t)
+__device__ __forceinline__ void wait_all_but_youngest_step(LowbitTileRegs& t)
 {
     if constexpr (BITS == 8) {
         static_assert(kLowbitOpsPerStep<8> == 5, "the wait below leaves 5 operations in flight");
@@ -189,7 +190,7 @@ __device__ __forceinline__ void wait_all_but_youngest_step(Fp8TileRegs& t)
 // Wait for every load in flight while both register sets are still owned by the pipeline: no
 // register of theirs may be handed to other code before its load has landed.
 template <int BITS>
-__device__ __forceinline__ void drain_tiles(Fp8TileRegs& t, Fp8TileRegs& u)
+__device__ __forceinline__ void drain_tiles(LowbitTileRegs& t, LowbitTileRegs& u)
 {
     if constexpr (BITS == 8)
         asm volatile("s_waitcnt vmcnt(0)"
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
             row0 = tile_row0<PAGED>(a, r.b, tile_t0, lookup_page<PAGED>(a, r.b, tile_t0));
             last = r.t1 - 1 - tile_t0;                                    // last valid row of this tile (>= 0)
         };
-        auto load_tile = [&](Fp8TileRegs& t, int tile) {
+        auto load_tile = [&](LowbitTileRegs& t, int tile) {
             int tile_t0, last; int64_t row0;
             tile_origin(tile, tile_t0, row0, last);
 #pragma unroll
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                     const int in_tile = row > last ? last : row;
                     const int c16 = (lane & 15) ^ (row & 15);
                     load_to_lds_16B((const unsigned char*)a.k + row0 * 256, (uint32_t)(in_tile * 256 + c16 * 16),
-                                    lds_addr0 + kFp8KBase + kslot * kFp8KSlotBytes + first_row * 256);
+                                    lds_addr0 + kLbKBase + kslot * kLbKSlotBytes + first_row * 256);
                 }
             } else {
                 const int first_row = 8 * wave;                                   // wave-uniform
@@ -268,11 +269,11 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                 const int in_tile = row > last ? last : row;
                 const int c16 = (lane & 7) ^ ((row >> 1) & 7);
                 load_to_lds_16B((const unsigned char*)a.k + row0 * 128, (uint32_t)(in_tile * 128 + c16 * 16),
-                                lds_addr0 + kFp8KBase + kslot * kFp8KSlotBytes + first_row * 128);
+                                lds_addr0 + kLbKBase + kslot * kLbKSlotBytes + first_row * 128);
             }
         };
         // Convert a tile's value codes to bf16 and write them into image `image`; the scales go beside it.
-        auto store_tile = [&](const Fp8TileRegs& t, int image) {
+        auto store_tile = [&](const LowbitTileRegs& t, int image) {
             if constexpr (BITS == 8) {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
@@ -288,14 +289,14 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                         half[w >> 1][4 * (w & 1) + 3] = p23[1];
                     }
                     const int key = prow & 15;                                 // row within its unit = prow (0..31)
-                    const int off = image * kFp8VImageBytes + i * 16384 + prow * 512 + ((pchunk ^ key) << 5);
+                    const int off = image * kLbVImageBytes + i * 16384 + prow * 512 + ((pchunk ^ key) << 5);
                     *LDS_AT(bf16x8, lds_base, off) = half[0];
                     *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
                 }
             } else {
                 // 32 elements = bf16 chunks 2*pchunk and 2*pchunk + 1 (32 bytes each) of row prow
                 const int key = prow & 15;
-                const int row_off = image * kFp8VImageBytes + (prow >> 5) * 16384 + (prow & 31) * 512;
+                const int row_off = image * kLbVImageBytes + (prow >> 5) * 16384 + (prow & 31) * 512;
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {                                  // word w: elements 8w .. 8w + 7
                     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                     *LDS_AT(bf16x8, lds_base, row_off + ((chunk ^ key) << 5) + (w & 1) * 16) = eight;
                 }
             }
-            if (threadIdx.x < 128) *LDS_AT(float, lds_base, kFp8ScaleBase + image * 512 + threadIdx.x * 4) = t.scale;
+            if (threadIdx.x < 128) *LDS_AT(float, lds_base, kLbScaleBase + image * 512 + threadIdx.x * 4) = t.scale;
         };
 
         WaveState st;
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
         // Step t consumes tile t (value image t & 1, key slot t % 3) while it converts the values of
         // tile t+1 into the other image and has the registers of tiles t+2, t+3 and the keys of tiles
         // t+1, t+2 in flight.  Prologue: what steps -2 and -1 would have issued.
-        Fp8TileRegs regs[2];
+        LowbitTileRegs regs[2];
         load_tile(regs[0], 0);
         load_tile(regs[1], 1);
         issue_keys(0, 0);
@@ -342,9 +343,9 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
             load_tile(regs[P ^ 1], t + 3);
             issue_keys(t + 2, kslot == 0 ? 2 : kslot - 1);                  // (t + 2) % 3, the slot tile t-1 has left
             auto unit = [&](int u) {
-                const int scales = kFp8ScaleBase + P * 512 + u * kUnitTokens * 4;
-                process_unit<BITS>(st, q, lds_base, kFp8KBase + kslot * kFp8KSlotBytes + u * kUnitTokens * kRowBytes,
-                                   P * kFp8VImageBytes + u * 16384, r.t0 + t * kTile + u * kUnitTokens, t1_mine,
+                const int scales = kLbScaleBase + P * 512 + u * kUnitTokens * 4;
+                process_unit<BITS>(st, q, lds_base, kLbKBase + kslot * kLbKSlotBytes + u * kUnitTokens * kRowBytes,
+                                   P * kLbVImageBytes + u * 16384, r.t0 + t * kTile + u * kUnitTokens, t1_mine,
                                    a.scale_log2e, n, g, scales, scales + 256);
             };
             if (QL == 2) { unit(0); unit(1); }

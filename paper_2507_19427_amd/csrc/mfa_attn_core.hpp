@@ -39,27 +39,17 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // s_waitcnt that constrains only the vector-memory counter: vmcnt(0).
 __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-// Direct global->LDS loads: `bytes` per lane land at lds_addr + bytes*lane (lds_addr is
-// wave-uniform and travels in M0).  Issued as inline assembly so that the compiler does not
-// make later LDS reads of *other* buffers wait for them; completion is awaited explicitly
-// with wait_vmem_all() followed by a workgroup barrier.  M0 is not otherwise live in these
-// kernels.  The s_nop covers the wait state required between writing M0 and an LDS-direct load.
-__device__ __forceinline__ void load_to_lds_16B(const void* gptr, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(gptr), "s"(lds_addr) : "memory");
-}
-// The same with the address given as a wave-uniform base (scalar registers) plus a 32-bit byte
-// offset per lane: no 64-bit vector arithmetic per load.
+// Direct global->LDS load: 16 bytes per lane land at lds_addr + 16*lane (lds_addr is wave-uniform
+// and travels in M0).  The global address is a wave-uniform base (scalar registers) plus a 32-bit
+// byte offset per lane: no 64-bit vector arithmetic per load.  Issued as inline assembly so that
+// the compiler does not make later LDS reads of *other* buffers wait for it; completion is
+// awaited explicitly (wait_vmem_all() or a counted s_waitcnt) followed by a workgroup barrier.
+// M0 is not otherwise live in these kernels.  The s_nop covers the wait state required between
+// writing M0 and an LDS-direct load.
 __device__ __forceinline__ void load_to_lds_16B(const void* sbase, uint32_t voff, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
-}
-__device__ __forceinline__ void load_to_lds_4B(const void* gptr, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-                 :: "v"(gptr), "s"(lds_addr) : "memory");
 }
 
 // max over the four lanes {n, n+16, n+32, n+48} that hold one head, without touching LDS:

@@ -71,14 +71,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
         const int k0 = k_begin + stage * kStageRows;
         const int rows_valid = (k_end - k0 < kStageRows) ? k_end - k0 : kStageRows;   // multiple of 32
         const int p8 = lane & 7;                                       // 16-byte position in the 128-byte row
+        const unsigned char* w_stage = (const unsigned char*)W + ((size_t)k0 * N + n0) * 2;   // wave-uniform
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int first_row = 8 * (8 * wave + i);                  // wave-uniform
             if (first_row < rows_valid) {
                 const int row = first_row + (lane >> 3);
                 const int c16 = ((((p8 >> 1) ^ w_key(row)) << 1) | (p8 & 1));
-                const unsigned char* src = (const unsigned char*)W + ((size_t)(k0 + row) * N + n0) * 2 + c16 * 16;
-                load_to_lds_16B(src, lds_addr0 + slot * kStageBytes + first_row * kRowBytes);
+                load_to_lds_16B(w_stage, (uint32_t)(row * N * 2 + c16 * 16), lds_addr0 + slot * kStageBytes + first_row * kRowBytes);
             }
         }
     };
