@@ -102,6 +102,37 @@ def test_fp8_mixed_lengths():
     _check(case, U.get_ctx(), U.TOL_FP8)
 
 
+@pytest.mark.parametrize("B,hi,kv_dtype", [(1000, 150, "bf16"), (4096, 70, "bf16"), (700, 200, "fp8")])
+def test_batches_between_513_and_4096_sequences(B, hi, kv_dtype):
+    """Above 512 sequences the lengths are scanned cooperatively through LDS instead of by every wave alone;
+    4096 is the largest batch the balanced schedule takes."""
+    _announce(f"B={B} {kv_dtype}, lengths 1..{hi}, some empty")
+    lens = _lens(400 + B, B, 1, hi, zeros=B // 20)
+    lens[0], lens[B - 1] = 0, hi                     # an empty first sequence, a full last one
+    case = W.make_contiguous_case("large", 401 + B, B=B, S=hi + 2, seq_lens=lens, kv_dtype=kv_dtype, poison=True)
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=256))
+    _check(case, ctx, U.TOL_FP8 if kv_dtype == "fp8" else U.TOL_BF16)
+    ctx.close()
+
+
+def test_two_query_tokens_with_a_thousand_sequences():
+    _announce("B=1000, two query tokens")
+    B = 1000
+    lens = _lens(451, B, 1, 130, zeros=40)
+    case = W.make_contiguous_case("large2", 452, B=B, S=136, seq_lens=lens, poison=True)
+    qm = W.make_multi_query(case, 2, 453)
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=256))
+    out = mfa.mfa_decode_attn_multi(ctx, qm.cuda(), case.k.cuda(), case.v.cuda(), case.seq_lens.cuda(), 130)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    import dataclasses
+    ref = np.stack([U.run_oracle(dataclasses.replace(case, q=qm[:, j].contiguous(),
+                                                     seq_lens=torch.clamp(case.seq_lens - (1 - j), min=0).to(torch.int32)))
+                    for j in range(2)], axis=1)
+    assert U.row_normalised_error(got, ref) <= U.TOL_BF16
+    ctx.close()
+
+
 def test_fixed_split_schedule_agrees(monkeypatch):
     """MFA_SCHEDULE=fixed selects the schedule with equal chunks per sequence; both must match the oracle."""
     _announce("fixed-split schedule")
