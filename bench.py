@@ -176,13 +176,16 @@ def build_workload(key, mfa, W, n_sets):
         w.kv_bytes_per_token = 520 if fp8 else 1024
         w.T, w.B, w.q_len = case.kv_tokens, B, 2
         w.extra_config = {"query_tokens_per_sequence": 2}
-    elif key in ("layer8k", "layer32k"):
+    elif key in ("layer8k", "layer32k", "layer8k_fp8", "layer32k_fp8"):
         # One whole attention layer of a decode step, the unit of the paper's attention-latency table
         # (Section 7.3: 64 sequences per GPU, context 8K / 32K): query path, key/value projection of the
         # new token and its cache record, attention over the lengthened cache, output projection.
-        S = 8192 if key == "layer8k" else 32768
+        # The _fp8 workloads keep the cache in e4m3 with per-token scales, as the paper's deployment does
+        # (its linears are 8-bit too; ours stay bf16).
+        fp8 = key.endswith("_fp8")
+        S = 8192 if key.startswith("layer8k") else 32768
         B = 64
-        case = W.make_contiguous_case(key, 7, B=B, S=S, poison=False)
+        case = W.make_contiguous_case(key, 7, B=B, S=S, kv_dtype="fp8" if fp8 else "bf16", poison=False)
         qc = W.make_query_proj_case(key + "_q", 5, B=B)
         gen = torch.Generator().manual_seed(8)
         w_kv = (torch.randn(W.D_MODEL, 2 * W.HEAD_DIM, generator=gen) * 0.02).to(torch.bfloat16)
@@ -190,6 +193,8 @@ def build_workload(key, mfa, W, n_sets):
         w.ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=S))
         x = qc.x.cuda()
         ks, vs = _roll_sets(case.k.cuda(), n_sets), _roll_sets(case.v.cuda(), n_sets)
+        kss = _roll_sets(case.k_scale.cuda(), n_sets) if fp8 else [None] * n_sets
+        vss = _roll_sets(case.v_scale.cuda(), n_sets) if fp8 else [None] * n_sets
         # every layer of a model has its own weights: rotate them like the cache
         wsets = [tuple(t.cuda() if j == 0 else t.cuda().clone() for t in (qc.w_qa, qc.w_qb, w_kv, w_o)) for j in range(n_sets)]
         old_lens = torch.full((B,), S - 1, dtype=torch.int32, device="cuda")
@@ -197,27 +202,33 @@ def build_workload(key, mfa, W, n_sets):
         q = torch.empty(B, 64, 256, dtype=torch.bfloat16, device="cuda")
         out = torch.empty(B, 64, 256, dtype=torch.float32, device="cuda")
         y = torch.empty(B, W.D_MODEL, dtype=torch.bfloat16, device="cuda")
-        attn = [mfa.PreparedDecodeAttn(w.ctx, q, ks[j], vs[j], new_lens, S, out) for j in range(n_sets)]
+        attn = [mfa.PreparedDecodeAttn(w.ctx, q, ks[j], vs[j], new_lens, S, out, k_scale=kss[j], v_scale=vss[j])
+                for j in range(n_sets)]
 
         def step(j):
             wa, wb, wkv, wo = wsets[j]
             mfa.mfa_query_proj(w.ctx, x, wa, wb, q_out=q)
-            mfa.mfa_kv_append(w.ctx, x, wkv, ks[j], vs[j], old_lens)
+            mfa.mfa_kv_append(w.ctx, x, wkv, ks[j], vs[j], old_lens, k_scale=kss[j], v_scale=vss[j])
             attn[j]()
             mfa.mfa_out_proj(w.ctx, out, wo, y=y)
         w.steps = [(lambda j=j: step(j)) for j in range(n_sets)]
         w.read_pairs = list(zip(ks, vs))
+        kv_name = "fp8 e4m3 KV with per-token scales" if fp8 else "bf16 KV"
         w.desc = ("attention layer of one decode step: B=64, query path 7168 -> 2048 -> 64x256, key/value projection "
-                  "7168 -> 2x256 + cache record, attention over ctx %d of contiguous bf16 KV, output projection "
-                  "16384 -> 7168; all weights bf16" % S)
-        w.metric = "KV tokens/s, MFA attention layer (linears + core attention), B=64, ctx %d, bf16, 1 GPU" % S
-        w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<false, 1>", 1024
+                  "7168 -> 2x256 + cache record, attention over ctx %d of contiguous %s, output projection "
+                  "16384 -> 7168; all weights bf16" % (S, kv_name))
+        w.metric = "KV tokens/s, MFA attention layer (linears + core attention), B=64, ctx %d, %s, 1 GPU" % (
+            S, "fp8 KV" if fp8 else "bf16")
+        w.dtype = "bf16 (fp8 e4m3 KV storage)" if fp8 else "bf16"
+        w.kernel = "mfa::decode_lowbit_kernel<false, 1, 8>" if fp8 else "mfa::decode_bf16_kernel<false, 1>"
+        w.kv_bytes_per_token = 520 if fp8 else 1024
         w.T, w.B = B * S, B
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S),
                           "weight_bytes_per_step": 2 * (qc.w_qa.numel() + qc.w_qb.numel() + w_kv.numel() + w_o.numel()),
                           "paper_layer_time_us": {"ctx": S, "H800": 281 if S == 8192 else 791, "H20": 438 if S == 8192 else 1452,
                                                   "A800": 531 if S == 8192 else 1484,
-                                                  "note": "attention-latency table of Section 7.3 (their linears use 8-bit weights)"}}
+                                                  "note": "attention-latency table of Section 7.3 (8-bit cache and 8-bit "
+                                                          "weights in the linears there)"}}
         w.keep = [x, wsets]
     else:
         raise ValueError(key)
@@ -229,7 +240,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "cfg2q2", "fp8q2", "fp4", "fp4q2", "layer8k", "layer32k"), default="cfg2")
+    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "cfg2q2", "fp8q2", "fp4", "fp4q2", "layer8k", "layer32k", "layer8k_fp8", "layer32k_fp8"), default="cfg2")
     ap.add_argument("--buffer-sets", type=int, default=None, help="distinct KV buffer sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
