@@ -95,7 +95,7 @@ Carve carve(const mfa_config* c, int32_t target)
     const int32_t n_attn = c->n_q_heads * c->head_dim;
     size_t partial_floats = (size_t)w.qproj.split_k * c->q_rank;
     const size_t kv_floats = (size_t)plan_linear(c->d_model, kKvWidth).split_k * kKvWidth;
-    const size_t o_floats = (size_t)plan_linear(n_attn, c->d_model).split_k * c->d_model;
+    const size_t o_floats = (size_t)std::max(std::max(plan_linear(n_attn, c->d_model, 1).split_k, plan_linear(n_attn, c->d_model, 2).split_k), plan_linear(n_attn, c->d_model, 4).split_k) * c->d_model;
     if (kv_floats > partial_floats) partial_floats = kv_floats;
     if (o_floats > partial_floats) partial_floats = o_floats;
     w.c = off;   off = align_up(off + partial_floats * w.rows_pad * sizeof(float), 256);
@@ -338,7 +338,7 @@ mfa_status mfa_out_proj(mfa_ctx* ctx, const float* attn_out, const void* w_o, vo
     OutProjArgs a{};
     a.attn = attn_out; a.w_o = w_o; a.y = y; a.ws_c = ctx->ws_c; a.ws_act = ctx->ws_chat;
     a.B = B; a.n_in = ctx->cfg.n_q_heads * ctx->cfg.head_dim; a.d_model = ctx->cfg.d_model;
-    a.plan = plan_linear(a.n_in, a.d_model);
+    a.plan = plan_out_proj(a.n_in, a.d_model, B);
     return launch_out_proj(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }
 

@@ -88,10 +88,12 @@ constexpr int kQProjRows = 128;   // rows of x one workgroup covers
 struct QProjPlan {
     int32_t split_k;      // K splits of a product whose fp32 partials go through the workspace
     int32_t k_per_split;
+    int32_t strips_per_wg;   // adjacent 64-column strips a workgroup owns: 1, or 2 / 4 (output projection with few rows)
 };
 // Split of the k range of y = x.W ([K] -> [N]) that fills the device: N/64 column strips times split_k
 // workgroups, about one per compute unit, at most 32 splits.
-QProjPlan plan_linear(int32_t K, int32_t N);
+QProjPlan plan_linear(int32_t K, int32_t N, int32_t strips_per_wg = 1);
+QProjPlan plan_out_proj(int32_t K, int32_t N, int32_t B);
 inline QProjPlan plan_qproj(int32_t d_model, int32_t q_rank) { return plan_linear(d_model, q_rank); }
 hipError_t prepare_query_proj_kernels();   // one-time function attributes (dynamic LDS size)
 hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream);

@@ -26,7 +26,6 @@ constexpr int kStageRows = 512;              // k rows per stage
 constexpr int kStageBytes = kStageRows * kRowBytes;   // 64 KB
 constexpr int kGemmLdsBytes = 2 * kStageBytes;
 constexpr int kGemmThreads = 512;
-constexpr int kStepsPerStage = kStageRows / 32;
 constexpr int kColBlocks = kStripN / 16;
 
 // Swizzle key of a W row in LDS: its 32-byte chunk c is stored at position c ^ key.  A transposing
@@ -42,7 +41,11 @@ __device__ __forceinline__ int w_key(int row) { return (((row >> 3) & 1) << 1) |
 //                  that the 16 rows x 64 B a wave loads per k step are contiguous.
 // MB = 2 or 1: 16-row blocks per wave; a workgroup covers 64 * MB rows of x (MB = 1 when there are
 //                  no more than 64 rows: half the x traffic and MFMA work).
-template <bool OUT_BF16, bool X_TILED, int MB>
+// NS = 1, 2 or 4: adjacent 64-column strips per workgroup.  A stage holds 512 / NS k rows of each; the x
+//                  fragments of a k step are multiplied into all NS strips, so x is fetched once per
+//                  64 * NS columns (for products whose x is as large as a workgroup's share of W: the
+//                  output projection).
+template <bool OUT_BF16, bool X_TILED, int MB, int NS>
 __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_t* __restrict__ X,
                                                                    const uint16_t* __restrict__ W,
                                                                    void* __restrict__ out, int M, int K, int N,
@@ -59,26 +62,34 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
     const int n = lane & 15;
     const int g = lane >> 4;
 
-    const int n0 = blockIdx.x * kStripN;
+    constexpr int kSubRows = kStageRows / NS;            // k rows of one stage
+    constexpr int kSubBytes = kSubRows * kRowBytes;       // one strip's part of a stage buffer
+    constexpr int kStepsPerStage = kSubRows / 32;
+    constexpr int kCols = kColBlocks * NS;                // 16-column blocks of the workgroup
+    const int n0 = blockIdx.x * kStripN * NS;
     const int m0 = blockIdx.y * 64 * MB;
     const int kz = blockIdx.z;
     const int k_begin = kz * k_per_split;
     const int k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
-    const int n_stages = (k_end - k_begin + kStageRows - 1) / kStageRows;
+    const int n_stages = (k_end - k_begin + kSubRows - 1) / kSubRows;
 
-    // Direct load of one stage of W: 64 loads of 8 rows; wave w issues loads 8w .. 8w+7.
+    // Direct load of one stage of W: 64 loads of 8 rows; wave w issues loads 8w .. 8w+7.  Load l brings rows
+    // 8*(l % (64/NS)) .. of strip l / (64/NS).
     auto issue_stage = [&](int stage, int slot) {
-        const int k0 = k_begin + stage * kStageRows;
-        const int rows_valid = (k_end - k0 < kStageRows) ? k_end - k0 : kStageRows;   // multiple of 32
+        const int k0 = k_begin + stage * kSubRows;
+        const int rows_valid = (k_end - k0 < kSubRows) ? k_end - k0 : kSubRows;       // multiple of 32
         const int p8 = lane & 7;                                       // 16-byte position in the 128-byte row
         const unsigned char* w_stage = (const unsigned char*)W + ((size_t)k0 * N + n0) * 2;   // wave-uniform
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int first_row = 8 * (8 * wave + i);                  // wave-uniform
+            const int l = 8 * wave + i;                                // wave-uniform
+            const int strip = l / (64 / NS);
+            const int first_row = 8 * (l % (64 / NS));
             if (first_row < rows_valid) {
                 const int row = first_row + (lane >> 3);
                 const int c16 = ((((p8 >> 1) ^ w_key(row)) << 1) | (p8 & 1));
-                load_to_lds_16B(w_stage, (uint32_t)(row * N * 2 + c16 * 16), lds_addr0 + slot * kStageBytes + first_row * kRowBytes);
+                load_to_lds_16B(w_stage, (uint32_t)(row * N * 2 + strip * kRowBytes + c16 * 16),
+                                lds_addr0 + slot * kStageBytes + strip * kSubBytes + first_row * kRowBytes);
             }
         }
     };
@@ -95,7 +106,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
         xrow[mb] = r < M ? r : M - 1;         // rows past M repeat the last one; their results are not stored
     }
     auto load_x_stage = [&](int stage, int buf) {
-        const int k0 = k_begin + stage * kStageRows;
+        const int k0 = k_begin + stage * kSubRows;
 #pragma unroll
         for (int j = 0; j < kMySteps; ++j) {
             int k = k0 + 32 * (2 * j + kh) + 8 * g;
@@ -109,11 +120,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
         }
     };
 
-    f32x4 acc[MB][kColBlocks];
+    f32x4 acc[MB][kCols];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < kColBlocks; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < kCols; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     const int a_lane_off = (8 * g + (n >> 2)) * kRowBytes + ((n & 3) << 3);   // row 8g + i, 8 bytes per lane
     const int a_key = ((g & 1) << 1) | ((n >> 3) & 1);                        // w_key of rows 8g + 4t + i
@@ -129,40 +140,46 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
                 f.nb[nb].h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
             }
     };
-    auto multiply = [&](const AFrag& f, int buf, int j) {
+    auto multiply = [&](const AFrag& f, int buf, int j, int strip) {
 #pragma unroll
         for (int nb = 0; nb < kColBlocks; ++nb)
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.nb[nb].v, xf[buf][mb][j], acc[mb][nb], 0, 0, 0);
+                acc[mb][strip * kColBlocks + nb] =
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.nb[nb].v, xf[buf][mb][j], acc[mb][strip * kColBlocks + nb], 0, 0, 0);
     };
-    // The A operands of the next own step are read from LDS while the current one is multiplied, so
-    // that the LDS latency hides behind eight MFMAs instead of stalling each pair.
+    // A stage is worked off in units (own k step j, strip): unit u = j * NS + strip.  The A operands of
+    // the next unit are read from LDS while the current one is multiplied, so that the LDS latency
+    // hides behind the MFMAs instead of stalling each pair.
+    constexpr int kUnits = kMySteps * NS;
+    static_assert(kUnits % 2 == 0, "units are taken in pairs");
     auto compute_stage = [&](int stage, int slot, int buf) {
-        const int k0 = k_begin + stage * kStageRows;
-        const int steps = ((k_end - k0 < kStageRows) ? k_end - k0 : kStageRows) / 32;
+        const int k0 = k_begin + stage * kSubRows;
+        const int steps = ((k_end - k0 < kSubRows) ? k_end - k0 : kSubRows) / 32;
         const int base = slot * kStageBytes;
+        auto unit_base = [&](int u) { return base + (u % NS) * kSubBytes; };
+        auto unit_step = [&](int u) { return 2 * (u / NS) + kh; };
         AFrag fa, fb;
         if (steps == kStepsPerStage) {                 // full stage: straight-line code
             // (the scheduling fences keep the compiler from sinking the reads back to their uses)
-            read_a(fa, base, kh);
+            read_a(fa, unit_base(0), unit_step(0));
 #pragma unroll
-            for (int j = 0; j < kMySteps; j += 2) {
-                read_a(fb, base, 2 * (j + 1) + kh);
+            for (int u = 0; u < kUnits; u += 2) {
+                read_a(fb, unit_base(u + 1), unit_step(u + 1));
                 __builtin_amdgcn_sched_barrier(0);
-                multiply(fa, buf, j);
+                multiply(fa, buf, u / NS, u % NS);
                 __builtin_amdgcn_sched_barrier(0);
-                if (j + 2 < kMySteps) read_a(fa, base, 2 * (j + 2) + kh);
+                if (u + 2 < kUnits) read_a(fa, unit_base(u + 2), unit_step(u + 2));
                 __builtin_amdgcn_sched_barrier(0);
-                multiply(fb, buf, j + 1);
+                multiply(fb, buf, (u + 1) / NS, (u + 1) % NS);
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < kMySteps; ++j)
-                if (2 * j + kh < steps) {
-                    read_a(fa, base, 2 * j + kh);
-                    multiply(fa, buf, j);
+            for (int u = 0; u < kUnits; ++u)
+                if (unit_step(u) < steps) {
+                    read_a(fa, unit_base(u), unit_step(u));
+                    multiply(fa, buf, u / NS, u % NS);
                 }
         }
     };
@@ -192,11 +209,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const uint16_
 
     // The two waves that share 32 rows (kh = 0, 1) hold sums over disjoint k steps: exchange halves
     // through LDS (the stage buffers are dead, no direct load is in flight); kh 0 finishes column
-    // blocks 0..1, kh 1 blocks 2..3.  Fixed order ((kh 0 part) + (kh 1 part)) keeps the result
+    // blocks of the lower half, kh 1 those of the upper half.  Fixed order ((kh 0 part) + (kh 1 part)) keeps the result
     // reproducible.
     __syncthreads();
     {
-        constexpr int kHalf = kColBlocks / 2;
+        constexpr int kHalf = kCols / 2;
         const int mine = (mp * 2 + kh) * MB * kHalf;  // slots of 1 KB: [row block][kHalf column blocks]
         const int theirs = (mp * 2 + (kh ^ 1)) * MB * kHalf;
 #pragma unroll
@@ -385,25 +402,41 @@ __global__ __launch_bounds__(256) void reduce_partials_bf16_kernel(const float* 
 
 namespace {
 
-// One streaming product: rows of x in tiles of 128 (64 when there are no more), strips of 64 columns, k splits.
+// One streaming product: rows of x in tiles of 128 (64 when there are no more), strips of 64 columns (groups of
+// two or four strips when the plan says so: fp32 partial output, k-step-major x, at most 64 rows), k splits.
 template <bool OUT_BF16, bool X_TILED>
 hipError_t launch_gemm(const void* X, const void* Wt, void* out, int M, int K, int N, const QProjPlan& plan, int split_k,
                        int rows_pad, hipStream_t stream)
 {
+    if (plan.strips_per_wg > 1) {
+        if constexpr (!OUT_BF16 && X_TILED) {
+            const int ns = plan.strips_per_wg;
+            if (M > 64 || (ns != 2 && ns != 4) || N % (ns * kStripN) != 0) return hipErrorInvalidValue;
+            if (ns == 2)
+                hipLaunchKernelGGL((gemm_stream_kernel<false, true, 1, 2>), dim3(N / (2 * kStripN), 1, split_k), dim3(kGemmThreads),
+                                   kGemmLdsBytes, stream, (const uint16_t*)X, (const uint16_t*)Wt, out, M, K, N, plan.k_per_split, rows_pad);
+            else
+                hipLaunchKernelGGL((gemm_stream_kernel<false, true, 1, 4>), dim3(N / (4 * kStripN), 1, split_k), dim3(kGemmThreads),
+                                   kGemmLdsBytes, stream, (const uint16_t*)X, (const uint16_t*)Wt, out, M, K, N, plan.k_per_split, rows_pad);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     if (M <= 64)
-        hipLaunchKernelGGL((gemm_stream_kernel<OUT_BF16, X_TILED, 1>), dim3(N / kStripN, 1, split_k), dim3(kGemmThreads), kGemmLdsBytes,
+        hipLaunchKernelGGL((gemm_stream_kernel<OUT_BF16, X_TILED, 1, 1>), dim3(N / kStripN, 1, split_k), dim3(kGemmThreads), kGemmLdsBytes,
                            stream, (const uint16_t*)X, (const uint16_t*)Wt, out, M, K, N, plan.k_per_split, rows_pad);
     else
-        hipLaunchKernelGGL((gemm_stream_kernel<OUT_BF16, X_TILED, 2>), dim3(N / kStripN, (M + 127) / 128, split_k), dim3(kGemmThreads),
+        hipLaunchKernelGGL((gemm_stream_kernel<OUT_BF16, X_TILED, 2, 1>), dim3(N / kStripN, (M + 127) / 128, split_k), dim3(kGemmThreads),
                            kGemmLdsBytes, stream, (const uint16_t*)X, (const uint16_t*)Wt, out, M, K, N, plan.k_per_split, rows_pad);
     return hipGetLastError();
 }
 
 }  // namespace
 
-QProjPlan plan_linear(int32_t K, int32_t N)
+QProjPlan plan_linear(int32_t K, int32_t N, int32_t strips_per_wg)
 {
-    const int32_t strips = N / kStripN;
+    const int32_t strips = N / (kStripN * strips_per_wg);
     int32_t want = 256 / (strips > 0 ? strips : 1);
     if (want < 1) want = 1;
     if (want > 32) want = 32;
@@ -412,14 +445,26 @@ QProjPlan plan_linear(int32_t K, int32_t N)
     QProjPlan p;
     p.k_per_split = per * 32;
     p.split_k = (ksteps + per - 1) / per;
+    p.strips_per_wg = strips_per_wg;
     return p;
+}
+
+// Output projection: with at most 64 rows a workgroup's share of the activations is as large as its share
+// of W, so groups of four strips (activations fetched once per 256 columns) pay for the fourfold k split
+// (16384 -> 7168 on MI355X: 66.6 us with single strips, 54.8 with pairs, 48.6 with fours).
+QProjPlan plan_out_proj(int32_t K, int32_t N, int32_t B)
+{
+    int32_t ns = 1;
+    if (B <= 64) ns = N % (4 * kStripN) == 0 ? 4 : (N % (2 * kStripN) == 0 ? 2 : 1);
+    return plan_linear(K, N, ns);
 }
 
 hipError_t prepare_query_proj_kernels()
 {
-    const void* kernels[] = {(const void*)gemm_stream_kernel<false, false, 1>, (const void*)gemm_stream_kernel<false, false, 2>,
-                             (const void*)gemm_stream_kernel<true, true, 1>, (const void*)gemm_stream_kernel<true, true, 2>,
-                             (const void*)gemm_stream_kernel<false, true, 1>, (const void*)gemm_stream_kernel<false, true, 2>};
+    const void* kernels[] = {(const void*)gemm_stream_kernel<false, false, 1, 1>, (const void*)gemm_stream_kernel<false, false, 2, 1>,
+                             (const void*)gemm_stream_kernel<true, true, 1, 1>, (const void*)gemm_stream_kernel<true, true, 2, 1>,
+                             (const void*)gemm_stream_kernel<false, true, 1, 1>, (const void*)gemm_stream_kernel<false, true, 2, 1>,
+                             (const void*)gemm_stream_kernel<false, true, 1, 2>, (const void*)gemm_stream_kernel<false, true, 1, 4>};
     for (const void* k : kernels) {
         const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
         if (e != hipSuccess) return e;
@@ -434,6 +479,7 @@ hipError_t launch_query_proj(const QProjArgs& a, hipStream_t stream)
     QProjPlan plan;
     plan.split_k = a.split_k;
     plan.k_per_split = a.k_per_split;
+    plan.strips_per_wg = 1;
     hipError_t e = launch_gemm<false, false>(a.x, a.w_qa, a.ws_c, a.B, a.d_model, a.q_rank, plan, a.split_k, rows_pad, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(rmsnorm_reduce_kernel, dim3(a.B), dim3(256), a.q_rank * sizeof(float), stream,
