@@ -185,7 +185,8 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& 
     if constexpr (BITS == 4) {
         // e2m1 keys x e4m3 query terms with unit block scales (E8M0 exponent 127)
         constexpr int kOne = 0x7F7F7F7F;
-        f32x4 slo[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
+        // both query terms go into one accumulator per 16-token block: two independent chains keep the MFMA
+        // pipe fed, and the small term is added first
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
 #pragma unroll
@@ -193,17 +194,14 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& 
                 const int row = kbase + tb * 2048 + n * 128;
                 const u32x4 k4 = *LDS_AT(u32x4, lds_base, row + (((4 * c + g) ^ ((n >> 1) & 7)) << 4));
                 const i32x8 kf = {(int)k4[0], (int)k4[1], (int)k4[2], (int)k4[3], 0, 0, 0, 0};
+                s[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf, q.lo[c], s[tb], 4, 0, 0, kOne, 0, kOne);
                 s[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf, q.hi[c], s[tb], 4, 0, 0, kOne, 0, kOne);
-                slo[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf, q.lo[c], slo[tb], 4, 0, 0, kOne, 0, kOne);
             }
         }
-        s[0] += slo[0];
-        s[1] += slo[1];
         scale_log2e *= q.inv_scale;
     } else if constexpr (BITS == 8) {
         // e4m3 x e4m3 with unit block scales (E8M0 exponent 127)
         constexpr int kOne = 0x7F7F7F7F;
-        f32x4 slo[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
 #pragma unroll
@@ -213,12 +211,10 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& 
                 union { i32x8 v; u32x4 h[2]; } kf;
                 kf.h[0] = *LDS_AT(u32x4, lds_base, row + ((m ^ n) << 4));
                 kf.h[1] = *LDS_AT(u32x4, lds_base, row + (((m + 1) ^ n) << 4));
+                s[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf.v, q.lo[c], s[tb], 0, 0, 0, kOne, 0, kOne);
                 s[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf.v, q.hi[c], s[tb], 0, 0, 0, kOne, 0, kOne);
-                slo[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf.v, q.lo[c], slo[tb], 0, 0, 0, kOne, 0, kOne);
             }
         }
-        s[0] += slo[0];                                  // four independent chains, joined here
-        s[1] += slo[1];
         scale_log2e *= q.inv_scale;
     } else {
         const int k_lane_off = n * 512;                 // K: row n of a 16-token block, swizzle key n
