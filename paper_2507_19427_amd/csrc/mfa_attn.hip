@@ -140,13 +140,13 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
 // are multiplied on the fp8/fp4 MFMA against the two-term query.  Values are multiplied by bf16
 // weights, so their codes are converted once per tile: every thread carries 32 bytes (8 bit: two
 // 16-byte pieces; 4 bit: one) of V and one per-token scale in registers from HBM, converts (exactly:
-// every e4m3 and e2m1 value is a bf16 value) and writes the swizzled bf16 rows into one of two value
-// images.
+// every e4m3 and e2m1 value is a bf16 value) and writes the bf16 rows into one of two value images
+// (padded rows in plain order: pv_unit).
 //
-// LDS: value image P (P = tile & 1) at P*32 KB, its unit g at + g*16 KB; key slot k (tile % 3) at
-// 64 KB + k*16 KB (4 bit: the first 8 KB of it); scale set P at 112 KB + P*512 B (64 key scales, then
+// LDS: value image P (P = tile & 1) at P*34 KB, its unit g at + g*17 KB; key slot k (tile % 3) at
+// 68 KB + k*16 KB (4 bit: the first 8 KB of it); scale set P at 116 KB + P*512 B (64 key scales, then
 // 64 value scales).
-constexpr int kLbVImageBytes = 2 * 16384;
+constexpr int kLbVImageBytes = 2 * kPaddedVUnitBytes;    // two units of 32 padded bf16 rows
 constexpr int kLbKBase = 2 * kLbVImageBytes;
 constexpr int kLbKSlotBytes = kTile * 256;
 constexpr int kLbKSlots = 3;
@@ -288,15 +288,13 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                         half[w >> 1][4 * (w & 1) + 2] = p23[0];
                         half[w >> 1][4 * (w & 1) + 3] = p23[1];
                     }
-                    const int key = prow & 15;                                 // row within its unit = prow (0..31)
-                    const int off = image * kLbVImageBytes + i * 16384 + prow * 512 + ((pchunk ^ key) << 5);
+                    const int off = image * kLbVImageBytes + i * kPaddedVUnitBytes + prow * kPaddedVRow + (pchunk << 5);
                     *LDS_AT(bf16x8, lds_base, off) = half[0];
                     *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
                 }
             } else {
                 // 32 elements = bf16 chunks 2*pchunk and 2*pchunk + 1 (32 bytes each) of row prow
-                const int key = prow & 15;
-                const int row_off = image * kLbVImageBytes + (prow >> 5) * 16384 + (prow & 31) * 512;
+                const int row_off = image * kLbVImageBytes + (prow >> 5) * kPaddedVUnitBytes + (prow & 31) * kPaddedVRow;
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {                                  // word w: elements 8w .. 8w + 7
                     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -306,7 +304,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                     const bf16x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 3);
                     const bf16x8 eight = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
                     const int chunk = 2 * pchunk + (w >> 1);
-                    *LDS_AT(bf16x8, lds_base, row_off + ((chunk ^ key) << 5) + (w & 1) * 16) = eight;
+                    *LDS_AT(bf16x8, lds_base, row_off + (chunk << 5) + (w & 1) * 16) = eight;
                 }
             }
             if (threadIdx.x < 128) *LDS_AT(float, lds_base, kLbScaleBase + image * 512 + threadIdx.x * 4) = t.scale;
@@ -345,7 +343,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
             auto unit = [&](int u) {
                 const int scales = kLbScaleBase + P * 512 + u * kUnitTokens * 4;
                 process_unit<BITS>(st, q, lds_base, kLbKBase + kslot * kLbKSlotBytes + u * kUnitTokens * kRowBytes,
-                                   P * kLbVImageBytes + u * 16384, r.t0 + t * kTile + u * kUnitTokens, t1_mine,
+                                   P * kLbVImageBytes + u * kPaddedVUnitBytes, r.t0 + t * kTile + u * kUnitTokens, t1_mine,
                                    a.scale_log2e, n, g, scales, scales + 256);
             };
             if (QL == 2) { unit(0); unit(1); }

@@ -164,21 +164,21 @@ __device__ __forceinline__ void load_split_q(QFrags<BITS>& q, const void* qptr, 
 
 // One 32-token unit: scores, online softmax, weighted sum.
 //   kbase      LDS byte offset of the unit's keys:
-//                bf16: 32 rows of 512 B, 16-byte chunk c of row r stored at c ^ (r & 15)
-//                fp8:  32 rows of 256 B of e4m3 codes, 16-byte chunk c of row r at c ^ (r & 15)
-//   vbase      LDS byte offset of the unit's values: 32 rows of 512 B of bf16 (fp8: the codes
-//              converted, unscaled), 32-byte chunk c of row r stored at c ^ (r & 15)
-//   unit_t0    index (within the sequence) of the unit's first token; tokens >= t1 are masked
+//                bf16:  32 rows of 512 B, 16-byte chunk c of row r stored at c ^ (r & 15)
+//                8 bit: 32 rows of 256 B of e4m3 codes, 16-byte chunk c of row r at c ^ (r & 15)
 //                4 bit: 32 rows of 128 B of packed e2m1 codes, 16-byte chunk c of row r at c ^ ((r >> 1) & 7)
+//   vbase      LDS byte offset of the unit's values in bf16 (8 / 4 bit: the codes expanded, unscaled); layout
+//              at pv_unit
+//   unit_t0    index (within the sequence) of the unit's first token; tokens >= t1 are masked
 //   8 / 4 bit  kscale/vscale point (LDS byte offsets) at the fp32 per-token scales of the unit's 32 tokens
+//
+// First half of a unit: scores, online softmax, rescale of what has been accumulated so far.  Returns
+// the unit's attention weights as the B operand of the weighted sum (8 tokens of this lane's head).
 template <int BITS>
-__device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& q, lds_ptr_t lds_base, int kbase,
-                                             int vbase, int unit_t0, int t1, float scale_log2e, int n, int g,
+__device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& q, lds_ptr_t lds_base, int kbase,
+                                             int unit_t0, int t1, float scale_log2e, int n, int g,
                                              int kscale_off, int vscale_off)
 {
-    const int v_row = 4 * g + (n >> 2);                 // V: row within a 16-token block = swizzle key
-    const int v_lane_off = v_row * 512 + ((n & 3) << 3);
-
     // ---- scores for 2 blocks of 16 tokens
     constexpr bool FP8 = BITS != 16;                     // 8-bit arithmetic on the scores, scales beside the codes
     f32x4 s[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
@@ -298,18 +298,42 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& 
 #pragma unroll
         for (int db = 0; db < 16; ++db) st.acc[db] *= alpha;
     }
+    return pf;
+}
 
-    // ---- O^T += V^T P^T over the unit's 32 tokens
+// Second half of a unit: O^T += V^T P^T over the unit's 32 tokens.
+//   PADDED = false (bf16 cache, rows written by direct loads): 512-byte rows, 32-byte chunk c of row r at c ^ (r & 15).
+//   PADDED = true  (8 / 4 bit caches, rows written from registers): rows kPaddedVRow = 544 bytes apart and in plain
+//                  order.  The 32 bytes of padding shift consecutive rows by eight banks, which spreads a transposing
+//                  read (4 rows x 32 bytes per 16 lanes, 8 rows per half wave) over all 64 banks as the XOR does,
+//                  and every operand address is then one lane register plus a compile-time offset.
+constexpr int kPaddedVRow = 544;
+constexpr int kPaddedVUnitBytes = kUnitTokens * kPaddedVRow;      // 17408
+template <bool PADDED>
+__device__ __forceinline__ void pv_unit(WaveState& st, lds_ptr_t lds_base, int vbase, const bf16x8& pf, int n, int g)
+{
+    const int v_row = 4 * g + (n >> 2);                 // V: row within a 16-token block (= swizzle key)
+    const int v_lane_off = v_row * (PADDED ? kPaddedVRow : 512) + ((n & 3) << 3);
 #pragma unroll
     for (int db = 0; db < 16; ++db) {
         union { bf16x8 v; s16x4 h[2]; } vf;
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
-            const int off = vbase + tb * 8192 + v_lane_off + ((db ^ v_row) << 5);
+            const int off = PADDED ? vbase + tb * 16 * kPaddedVRow + v_lane_off + (db << 5)
+                                   : vbase + tb * 8192 + v_lane_off + ((db ^ v_row) << 5);
             vf.h[tb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
         }
         st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf, st.acc[db], 0, 0, 0);
     }
+}
+
+template <int BITS>
+__device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& q, lds_ptr_t lds_base, int kbase,
+                                             int vbase, int unit_t0, int t1, float scale_log2e, int n, int g,
+                                             int kscale_off, int vscale_off)
+{
+    const bf16x8 pf = score_unit<BITS>(st, q, lds_base, kbase, unit_t0, t1, scale_log2e, n, g, kscale_off, vscale_off);
+    pv_unit<BITS != 16>(st, lds_base, vbase, pf, n, g);
 }
 
 // After the last tile the two waves that share 16 heads (grp 0 and 1: the two token halves of
