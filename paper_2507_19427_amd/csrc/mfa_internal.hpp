@@ -88,7 +88,7 @@ constexpr int kQProjRows = 128;   // rows of x one workgroup covers
 struct QProjPlan {
     int32_t split_k;      // K splits of a product whose fp32 partials go through the workspace
     int32_t k_per_split;
-    int32_t strips_per_wg;   // adjacent 64-column strips a workgroup owns: 1, or 2 / 4 (output projection with few rows)
+    int32_t strips_per_wg;   // adjacent 64-column strips a workgroup owns: 1, or 2 / 4 (output projection with at most 128 / 64 rows)
 };
 // Split of the k range of y = x.W ([K] -> [N]) that fills the device: N/64 column strips times split_k
 // workgroups, about one per compute unit, at most 32 splits.

@@ -403,7 +403,7 @@ __global__ __launch_bounds__(256) void reduce_partials_bf16_kernel(const float* 
 namespace {
 
 // One streaming product: rows of x in tiles of 128 (64 when there are no more), strips of 64 columns (groups of
-// two or four strips when the plan says so: fp32 partial output, k-step-major x, at most 64 rows), k splits.
+// two or four strips when the plan says so: fp32 partial output, k-step-major x, at most 128 rows), k splits.
 template <bool OUT_BF16, bool X_TILED>
 hipError_t launch_gemm(const void* X, const void* Wt, void* out, int M, int K, int N, const QProjPlan& plan, int split_k,
                        int rows_pad, hipStream_t stream)
@@ -411,14 +411,15 @@ hipError_t launch_gemm(const void* X, const void* Wt, void* out, int M, int K, i
     if (plan.strips_per_wg > 1) {
         if constexpr (!OUT_BF16 && X_TILED) {
             const int ns = plan.strips_per_wg;
-            if (M > 64 || (ns != 2 && ns != 4) || N % (ns * kStripN) != 0) return hipErrorInvalidValue;
-            if (ns == 2)
-                hipLaunchKernelGGL((gemm_stream_kernel<false, true, 1, 2>), dim3(N / (2 * kStripN), 1, split_k), dim3(kGemmThreads),
-                                   kGemmLdsBytes, stream, (const uint16_t*)X, (const uint16_t*)Wt, out, M, K, N, plan.k_per_split, rows_pad);
-            else
-                hipLaunchKernelGGL((gemm_stream_kernel<false, true, 1, 4>), dim3(N / (4 * kStripN), 1, split_k), dim3(kGemmThreads),
-                                   kGemmLdsBytes, stream, (const uint16_t*)X, (const uint16_t*)Wt, out, M, K, N, plan.k_per_split, rows_pad);
-            return hipGetLastError();
+            if (M > 128 || (ns != 2 && ns != 4) || (ns == 4 && M > 64) || N % (ns * kStripN) != 0) return hipErrorInvalidValue;
+            const dim3 grid(N / (ns * kStripN), 1, split_k);
+            const void* kernel = M <= 64 ? (ns == 2 ? (const void*)gemm_stream_kernel<false, true, 1, 2> : (const void*)gemm_stream_kernel<false, true, 1, 4>)
+                                         : (const void*)gemm_stream_kernel<false, true, 2, 2>;
+            const uint16_t* xp = (const uint16_t*)X;
+            const uint16_t* wp = (const uint16_t*)Wt;
+            int k_per_split = plan.k_per_split;
+            void* params[] = {&xp, &wp, &out, &M, &K, &N, &k_per_split, &rows_pad};
+            return hipLaunchKernel(kernel, grid, dim3(kGemmThreads), params, kGemmLdsBytes, stream);
         } else {
             return hipErrorInvalidValue;
         }
@@ -451,11 +452,13 @@ QProjPlan plan_linear(int32_t K, int32_t N, int32_t strips_per_wg)
 
 // Output projection: with at most 64 rows a workgroup's share of the activations is as large as its share
 // of W, so groups of four strips (activations fetched once per 256 columns) pay for the fourfold k split
-// (16384 -> 7168 on MI355X: 66.6 us with single strips, 54.8 with pairs, 48.6 with fours).
+// (16384 -> 7168 on MI355X: 66.6 us with single strips, 54.8 with pairs, 48.6 with fours).  With 65 to 128
+// rows: pairs (whole call 105 -> 82 us).
 QProjPlan plan_out_proj(int32_t K, int32_t N, int32_t B)
 {
     int32_t ns = 1;
     if (B <= 64) ns = N % (4 * kStripN) == 0 ? 4 : (N % (2 * kStripN) == 0 ? 2 : 1);
+    else if (B <= 128) ns = N % (2 * kStripN) == 0 ? 2 : 1;      // (four strips of 128 rows do not fit the registers)
     return plan_linear(K, N, ns);
 }
 
@@ -464,7 +467,8 @@ hipError_t prepare_query_proj_kernels()
     const void* kernels[] = {(const void*)gemm_stream_kernel<false, false, 1, 1>, (const void*)gemm_stream_kernel<false, false, 2, 1>,
                              (const void*)gemm_stream_kernel<true, true, 1, 1>, (const void*)gemm_stream_kernel<true, true, 2, 1>,
                              (const void*)gemm_stream_kernel<false, true, 1, 1>, (const void*)gemm_stream_kernel<false, true, 2, 1>,
-                             (const void*)gemm_stream_kernel<false, true, 1, 2>, (const void*)gemm_stream_kernel<false, true, 1, 4>};
+                             (const void*)gemm_stream_kernel<false, true, 1, 2>, (const void*)gemm_stream_kernel<false, true, 1, 4>,
+                             (const void*)gemm_stream_kernel<false, true, 2, 2>};
     for (const void* k : kernels) {
         const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
         if (e != hipSuccess) return e;

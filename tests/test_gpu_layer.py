@@ -94,7 +94,7 @@ def test_record_is_bit_exact_bf16_and_skips_rows_outside_the_cache():
     assert (kb == 0).all() and (vb == 0).all()
 
 
-@pytest.mark.parametrize("B,d_model", [(5, 256), (64, 256), (40, 384), (33, 448), (130, 448), (64, 7168), (128, 7168)])
+@pytest.mark.parametrize("B,d_model", [(5, 256), (64, 256), (40, 384), (100, 384), (33, 448), (130, 448), (64, 7168), (128, 7168)])
 def test_kv_projection_and_record_end_to_end(B, d_model):
     print(f"\n[case] kv append B={B} d_model={d_model}", flush=True)
     g = torch.Generator().manual_seed(410 + B)
@@ -131,7 +131,7 @@ def test_kv_projection_and_record_end_to_end(B, d_model):
     assert np.allclose(sc, amax[:, [0, 256]] / 448.0, rtol=5e-3)
 
 
-@pytest.mark.parametrize("B,d_model", [(5, 256), (64, 256), (40, 384), (33, 448), (130, 448), (64, 7168), (128, 7168)])
+@pytest.mark.parametrize("B,d_model", [(5, 256), (64, 256), (40, 384), (100, 384), (33, 448), (130, 448), (64, 7168), (128, 7168)])
 def test_output_projection(B, d_model):
     print(f"\n[case] out proj B={B} d_model={d_model}", flush=True)
     g = torch.Generator().manual_seed(420 + B)
