@@ -58,3 +58,32 @@ def test_fp8_without_scales_is_rejected():
     with pytest.raises(mfa.MfaError) as e:
         mfa.mfa_decode_attn(ctx, case.q.cuda(), case.k.cuda(), case.v.cuda(), case.seq_lens.cuda(), 64)
     assert e.value.status == mfa.MFA_ERR_INVALID_ARG
+
+
+def test_fp8_run_to_run_determinism_and_prepared_calls():
+    """Same inputs, same bits; and the pre-marshalled call objects bench.py uses give the same result as the
+    checked wrappers (single query token and a pair)."""
+    print("\n[case] fp8 determinism / prepared calls", flush=True)
+    import paper_2507_19427_amd as mfa
+    lens = [700, 64, 1500, 2, 129, 0]
+    case = W.make_contiguous_case("fp8det", 911, B=len(lens), S=1504, seq_lens=lens, kv_dtype="fp8", poison=True)
+    ctx = U.get_ctx()
+    a = U.run_gpu(ctx, case)
+    b = U.run_gpu(ctx, case)
+    assert np.array_equal(a, b)
+    d = U.to_dev
+    q, k, v, ks, vs, sl = d(case.q), d(case.k), d(case.v), d(case.k_scale), d(case.v_scale), d(case.seq_lens)
+    out = torch.empty(len(lens), 64, 256, dtype=torch.float32, device="cuda")
+    call = mfa.PreparedDecodeAttn(ctx, q, k, v, sl, 1500, out, k_scale=ks, v_scale=vs)
+    out.fill_(float("nan"))
+    call()
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), a)
+    qm = d(W.make_multi_query(case, 2, 912))
+    want = mfa.mfa_decode_attn_multi(ctx, qm, k, v, sl, 1500, k_scale=ks, v_scale=vs)
+    out2 = torch.full((len(lens), 2, 64, 256), float("nan"), dtype=torch.float32, device="cuda")
+    call2 = mfa.PreparedDecodeAttn(ctx, qm, k, v, sl, 1500, out2, k_scale=ks, v_scale=vs)
+    out2.fill_(float("nan"))
+    call2()
+    torch.cuda.synchronize()
+    assert torch.equal(out2, want)
