@@ -277,3 +277,34 @@ def test_row_subset_matches_full(oracle):
     sub = _run(oracle, case, rows=rows)
     for i, (bb, hh) in enumerate(rows):
         assert np.array_equal(sub[i], full[bb, hh])
+
+
+@pytest.mark.parametrize("q_len", [2, 3, 4])
+def test_several_query_tokens_equal_causal_attention_over_the_new_tokens(oracle, q_len):
+    """A decode step with q_len new tokens per sequence (Section 5.2, multi-token prediction) is checked on the
+    GPU against the single-token oracle called once per token with the length L - (q_len - 1 - j).  That
+    composition is pinned here against torch's fp64 scaled_dot_product_attention with a mask that is causal
+    among the last q_len positions, and against ragged lengths including L < q_len."""
+    lens = [40, 1, 2, 3, 17, 0]
+    case = W.make_contiguous_case("mt", 33 + q_len, B=len(lens), S=40, seq_lens=lens, poison=False, H=4, D=32, scale=0.2)
+    qm = W.make_multi_query(case, q_len, 34)
+    B, H, D = case.q.shape
+    k, v = _dequant(case)
+    for b, L in enumerate(lens):
+        for j in range(q_len):
+            Lj = max(L - (q_len - 1 - j), 0)
+            sub = W.AttnCase(name="s", q=qm[b:b + 1, j].contiguous(), seq_lens=torch.tensor([Lj], dtype=torch.int32),
+                             kv_dtype="bf16", k=case.k[b:b + 1], v=case.v[b:b + 1], scale=case.scale)
+            got = _run(oracle, sub)[0]
+            if Lj == 0:
+                assert (got == 0).all()
+                continue
+            # rows of the mask: query token j sees positions < L - (q_len - 1 - j)
+            kk = torch.from_numpy(k[b, :L])[None, None].expand(1, H, L, D)
+            vv = torch.from_numpy(v[b, :L])[None, None].expand(1, H, L, D)
+            mask = torch.zeros(q_len, L, dtype=torch.bool)
+            for jj in range(q_len):
+                mask[jj, :max(L - (q_len - 1 - jj), 0)] = True
+            qq = qm[b].double().permute(1, 0, 2)[None]                      # [1, H, q_len, D]
+            ref = torch.nn.functional.scaled_dot_product_attention(qq, kk, vv, attn_mask=mask[None, None], scale=0.2)
+            assert np.abs(got - ref[0, :, j].numpy()).max() <= 1e-6
