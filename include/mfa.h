@@ -142,7 +142,7 @@ MFA_API mfa_status mfa_kv_append(mfa_ctx* ctx, const void* x, const void* w_kv, 
 
 /* The same into a paged cache: the row is (seq_lens[b] % page_size) of page
  * block_table[b][seq_lens[b] / page_size]; a block index at or past
- * max_blocks_per_seq is not written. */
+ * max_blocks_per_seq, or a page id outside [0, n_pages), is not written. */
 MFA_API mfa_status mfa_kv_append_paged(mfa_ctx* ctx, const void* x, const void* w_kv, mfa_kv_dtype kv_dtype, void* k_pool,
                                void* v_pool, float* k_scale_pool, float* v_scale_pool, int32_t n_pages,
                                const int32_t* block_table, int32_t max_blocks_per_seq, const int32_t* seq_lens,
@@ -205,6 +205,9 @@ MFA_API mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_ca
  * (j % page_size) of page block_table[b][j / page_size].
  *   k_pool, v_pool            [n_pages, page_size, head_dim] in kv_dtype (fp4: head_dim/2 bytes per row)
  *   k_scale_pool, v_scale_pool  fp32 [n_pages, page_size]; NULL for bf16
+ *   block_table  int32 [B, max_blocks_per_seq] on the device; entries past a sequence's last page are
+ *            never read.  A page id outside [0, n_pages) is clamped into that range: the result of that
+ *            sequence is then meaningless, but no memory outside the pools is touched.
  *   block_table  int32 [B, max_blocks_per_seq] on the device; entries at or past
  *                ceil(seq_lens[b] / page_size) are never read (may be -1)
  *   max_blocks_per_seq >= ceil(max_seq_len_hint / page_size)

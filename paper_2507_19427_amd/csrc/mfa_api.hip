@@ -311,6 +311,7 @@ mfa_status mfa_kv_append_paged(mfa_ctx* ctx, const void* x, const void* w_kv, mf
     fill_kv_append(ctx, a, x, w_kv, k_pool, v_pool, k_scale_pool, v_scale_pool, seq_lens, B);
     a.block_table = block_table;
     a.max_blocks_per_seq = max_blocks_per_seq;
+    a.n_pages = n_pages;
     return launch_kv_append(a, kv_dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }
 
@@ -325,6 +326,7 @@ mfa_status mfa_debug_kv_record(mfa_ctx* ctx, const float* kv, mfa_kv_dtype kv_dt
     fill_kv_append(ctx, a, nullptr, nullptr, k_cache, v_cache, k_scale, v_scale, seq_lens, B);
     a.block_table = block_table;
     a.max_blocks_per_seq = max_blocks_per_seq;
+    a.n_pages = INT32_MAX;                                  // the test aid has no pool size: ids are taken as given
     a.seq_stride_tokens = kv_seq_stride_tokens;
     return launch_kv_record(a, kv, kv_dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }
@@ -389,7 +391,7 @@ mfa_status mfa_decode_attn_paged_multi(mfa_ctx* ctx, const void* q, const void* 
     AttnArgs a{};
     a.q = q; a.k = k_pool; a.v = v_pool; a.k_scale = k_scale_pool; a.v_scale = v_scale_pool;
     a.seq_lens = seq_lens; a.block_table = block_table; a.out = out;
-    a.seq_stride_tokens = 0; a.max_blocks_per_seq = max_blocks_per_seq;
+    a.seq_stride_tokens = 0; a.max_blocks_per_seq = max_blocks_per_seq; a.n_pages = n_pages;
     fill_common(ctx, a, B, max_seq_len_hint);
     a.q_len = q_len;
     const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream), ctx->ev_before, ctx->ev_after);
@@ -420,7 +422,7 @@ mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_t row_by
     if (dst_seq_stride_tokens < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(pool) & 3u) || (reinterpret_cast<uintptr_t>(dst) & 3u)) return MFA_ERR_INVALID_ARG;
     if (!on_device(ctx)) return MFA_ERR_INVALID_ARG;
-    const hipError_t e = launch_gather_paged(pool, row_bytes, block_table, max_blocks_per_seq, seq_lens,
+    const hipError_t e = launch_gather_paged(pool, row_bytes, block_table, max_blocks_per_seq, n_pages, seq_lens,
                                              max_seq_len_hint, B, dst, dst_seq_stride_tokens,
                                              static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;

@@ -40,7 +40,9 @@ __device__ __forceinline__ int lookup_page(const AttnArgs& a, int b, int tile_t0
     // read through the constant address space: the table is not written while the kernel runs, and a
     // uniform index then makes this a scalar load, which the vector-memory waits do not have to cover
     typedef const __attribute__((address_space(4))) int32_t* const_table_t;
-    return PAGED ? ((const_table_t)a.block_table)[(size_t)b * a.max_blocks_per_seq + tile_t0 / kPage] : 0;
+    if (!PAGED) return 0;
+    const int page = ((const_table_t)a.block_table)[(size_t)b * a.max_blocks_per_seq + tile_t0 / kPage];
+    return page < 0 ? 0 : (page >= a.n_pages ? a.n_pages - 1 : page);      // a bad id reads a wrong page, never outside the pool
 }
 
 template <bool PAGED>
@@ -438,7 +440,7 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 // Copy the logical rows of every sequence out of a paged pool (test aid).
 __global__ __launch_bounds__(256) void gather_paged_kernel(const uint32_t* pool, int32_t row_words,
                                                            const int32_t* block_table, int32_t max_blocks_per_seq,
-                                                           const int32_t* seq_lens, int32_t hint, uint32_t* dst,
+                                                           int32_t n_pages, const int32_t* seq_lens, int32_t hint, uint32_t* dst,
                                                            int64_t dst_seq_stride_tokens)
 {
     const int b = blockIdx.y;
@@ -448,7 +450,8 @@ __global__ __launch_bounds__(256) void gather_paged_kernel(const uint32_t* pool,
     const int tok0 = blk * kPage;
     if (tok0 >= L) return;
     const int n_tok = (L - tok0 < kPage) ? L - tok0 : kPage;
-    const int page = block_table[(size_t)b * max_blocks_per_seq + blk];
+    int page = block_table[(size_t)b * max_blocks_per_seq + blk];
+    page = page < 0 ? 0 : (page >= n_pages ? n_pages - 1 : page);
     const uint32_t* src = pool + (size_t)page * kPage * row_words;
     uint32_t* d = dst + ((size_t)b * dst_seq_stride_tokens + tok0) * row_words;
     for (int i = threadIdx.x; i < n_tok * row_words; i += 256) d[i] = src[i];
@@ -565,12 +568,12 @@ hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStrea
 }
 
 hipError_t launch_gather_paged(const void* pool, int32_t row_bytes, const int32_t* block_table,
-                               int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t max_seq_len_hint,
+                               int32_t max_blocks_per_seq, int32_t n_pages, const int32_t* seq_lens, int32_t max_seq_len_hint,
                                int32_t B, void* dst, int64_t dst_seq_stride_tokens, hipStream_t stream)
 {
     const int blocks = (max_seq_len_hint + kPage - 1) / kPage;
     hipLaunchKernelGGL(gather_paged_kernel, dim3((unsigned)blocks, (unsigned)B), dim3(256), 0, stream,
-                       (const uint32_t*)pool, row_bytes / 4, block_table, max_blocks_per_seq, seq_lens,
+                       (const uint32_t*)pool, row_bytes / 4, block_table, max_blocks_per_seq, n_pages, seq_lens,
                        max_seq_len_hint, (uint32_t*)dst, dst_seq_stride_tokens);
     return hipGetLastError();
 }

@@ -52,6 +52,7 @@ struct AttnArgs {
     int32_t* ws_seg;               // balanced schedule: per sequence (first partial slot, number of partials)
     int64_t seq_stride_tokens;     // contiguous only
     int32_t max_blocks_per_seq;    // paged only
+    int32_t n_pages;               // paged only: page ids are clamped into [0, n_pages) when read, rows with ids outside are not written
     int32_t B;
     int32_t q_len;                 // query tokens per sequence (q and out are [B, q_len, 64, 256])
     int32_t q0;                    // first query token this launch works on: a launch takes token q0 (q_len == 1)
@@ -112,6 +113,7 @@ struct KvAppendArgs {
     float* ws_c;                   // fp32 [split_k][B_pad][512]
     int64_t seq_stride_tokens;     // contiguous only
     int32_t max_blocks_per_seq;    // paged only
+    int32_t n_pages;               // paged only: page ids are clamped into [0, n_pages) when read, rows with ids outside are not written
     int32_t B, d_model;
     QProjPlan plan;
 };
@@ -132,7 +134,7 @@ struct OutProjArgs {
 hipError_t launch_out_proj(const OutProjArgs& a, hipStream_t stream);
 
 hipError_t launch_gather_paged(const void* pool, int32_t row_bytes, const int32_t* block_table,
-                               int32_t max_blocks_per_seq, const int32_t* seq_lens, int32_t max_seq_len_hint,
+                               int32_t max_blocks_per_seq, int32_t n_pages, const int32_t* seq_lens, int32_t max_seq_len_hint,
                                int32_t B, void* dst, int64_t dst_seq_stride_tokens, hipStream_t stream);
 
 }  // namespace mfa

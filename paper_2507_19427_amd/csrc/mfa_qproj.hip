@@ -328,7 +328,9 @@ __global__ __launch_bounds__(kHeadDim) void kv_record_kernel(const float* __rest
     if (PAGED) {
         const int blk = pos / kPage;
         if (pos < 0 || blk >= a.max_blocks_per_seq) return;
-        row = (int64_t)a.block_table[(size_t)b * a.max_blocks_per_seq + blk] * kPage + pos % kPage;
+        const int page = a.block_table[(size_t)b * a.max_blocks_per_seq + blk];
+        if (page < 0 || page >= a.n_pages) return;                  // never write outside the pools
+        row = (int64_t)page * kPage + pos % kPage;
     } else {
         if (pos < 0 || pos >= a.seq_stride_tokens) return;
         row = (int64_t)b * a.seq_stride_tokens + pos;

@@ -165,3 +165,35 @@ def test_argument_errors_through_the_c_abi():
     assert call(dt=1) == mfa.MFA_ERR_INVALID_ARG                                    # fp8 without scales
     assert call(dt=7) == mfa.MFA_ERR_INVALID_ARG
     torch.cuda.synchronize()
+
+
+def test_page_ids_outside_the_pool_touch_nothing_outside_it():
+    """A block table with garbage ids for one sequence: reads are clamped into the pool (that sequence's result
+    is meaningless), the other sequences are unaffected, and the append writes nothing for a bad id."""
+    print("\n[case] bad page ids", flush=True)
+    lens = [200, 130, 64, 300]
+    case = W.make_paged_case("badids", 95, lens, spare_pages=3, poison=False)
+    ref = U.run_oracle(case)
+    bad = case.block_table.clone()
+    bad[1, 0], bad[1, 1], bad[1, 2] = -7, 2 ** 30, case.k_pool.shape[0]
+    ctx = U.get_ctx()
+    d = U.to_dev
+    out = mfa.mfa_decode_attn_paged(ctx, d(case.q), d(case.k_pool), d(case.v_pool), d(bad), d(case.seq_lens), 300)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, 2, 3):
+        assert U.row_normalised_error(got[b], ref[b]) <= U.TOL_BF16
+    # append: sequence 1's next row would land in page id 2**30 -> skipped; the others are written
+    x = torch.randn(4, 7168, generator=torch.Generator().manual_seed(96)).to(torch.bfloat16)
+    w_kv = (torch.randn(7168, 512, generator=torch.Generator().manual_seed(97)) * 0.02).to(torch.bfloat16)
+    kp, vp = d(case.k_pool).clone(), d(case.v_pool).clone()
+    before = kp.clone()
+    at = torch.tensor([64, 64, 10, 70], dtype=torch.int32)       # row 0 of block 1, ..., block 1 of sequence 1 is the bad id
+    mfa.mfa_kv_append_paged(ctx, d(x), d(w_kv), kp, vp, d(bad), d(at))
+    torch.cuda.synchronize()
+    changed = (kp != before).any(dim=2).cpu()                     # [n_pages, page]
+    want = torch.zeros_like(changed)
+    for b in (0, 2, 3):
+        want[int(case.block_table[b, int(at[b]) // 64]), int(at[b]) % 64] = True
+    assert torch.equal(changed, want)
