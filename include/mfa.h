@@ -205,11 +205,11 @@ MFA_API mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_ca
  * (j % page_size) of page block_table[b][j / page_size].
  *   k_pool, v_pool            [n_pages, page_size, head_dim] in kv_dtype (fp4: head_dim/2 bytes per row)
  *   k_scale_pool, v_scale_pool  fp32 [n_pages, page_size]; NULL for bf16
- *   block_table  int32 [B, max_blocks_per_seq] on the device; entries past a sequence's last page are
- *            never read.  A page id outside [0, n_pages) is clamped into that range: the result of that
- *            sequence is then meaningless, but no memory outside the pools is touched.
  *   block_table  int32 [B, max_blocks_per_seq] on the device; entries at or past
- *                ceil(seq_lens[b] / page_size) are never read (may be -1)
+ *                ceil(seq_lens[b] / page_size) are never read (may be -1).  A page id
+ *                outside [0, n_pages) that is read is clamped into that range: the result
+ *                of that sequence is then meaningless, but no memory outside the pools
+ *                is touched.
  *   max_blocks_per_seq >= ceil(max_seq_len_hint / page_size)
  * Other arguments as mfa_decode_attn.  For the same tokens the result is
  * bitwise equal to mfa_decode_attn's on the gathered contiguous cache with the
