@@ -469,15 +469,26 @@ struct Schedule {
     int b;              // next sequence to look at
 };
 
+// floor(a / d) for 32-bit operands without the long emulated integer division (some hundred scalar
+// instructions ahead of every workgroup's first load): double-precision reciprocal, then one step of
+// correction in integers (the estimate is off by at most one).
+__device__ __forceinline__ unsigned div_floor_u32(unsigned a, unsigned d)
+{
+    unsigned q = (unsigned)((double)a * __builtin_amdgcn_rcp((double)d));
+    const unsigned long long prod = (unsigned long long)q * d;
+    if (prod > a) --q;
+    else if (prod + d <= a) ++q;
+    return q;
+}
 // floor(x * N / G) and the workgroup of a tile, in 32 bits when the products fit.
 __device__ __forceinline__ int scaled_floor(int x, int N, int G)
 {
-    if (N < (1 << 20) && x <= (1 << 11)) return (int)((unsigned)x * (unsigned)N / (unsigned)G);
+    if (N < (1 << 20) && x <= (1 << 11)) return (int)div_floor_u32((unsigned)x * (unsigned)N, (unsigned)G);
     return (int)((unsigned long long)x * (unsigned long long)N / (unsigned long long)G);
 }
 __device__ __forceinline__ int wg_of_tile(int t, int G, int N)
 {
-    if (N < (1 << 20) && G <= (1 << 11)) return (int)((((unsigned)t + 1u) * (unsigned)G - 1u) / (unsigned)N);
+    if (N < (1 << 20) && G <= (1 << 11)) return (int)div_floor_u32(((unsigned)t + 1u) * (unsigned)G - 1u, (unsigned)N);
     return (int)((((unsigned long long)t + 1ull) * (unsigned long long)G - 1ull) / (unsigned long long)N);
 }
 
