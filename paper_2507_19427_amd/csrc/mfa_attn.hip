@@ -366,7 +366,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
 // Merge the partial results of one sequence (fixed splits: slots b*n_splits ...; balanced schedule:
 // the slots recorded by the workgroup that held the sequence's first tile):
 //   out = sum_s 2^(m_s - m*) acc_s / sum_s 2^(m_s - m*) l_s,  m* = max_s m_s,
-// summed in split order.  One thread per float4 of the partial's lane-order layout; splits are
+// summed in split order (m* is reached batch by batch, rescaling what has been summed).  One thread per float4 of the partial's lane-order layout; splits are
 // taken four at a time so that their loads are independent and in flight together.
 __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 {
@@ -404,17 +404,9 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
     const float2* ml_base = (const float2*)a.ws_ml + slot0 * kHeads + h;
     const float4* acc_base = (const float4*)a.ws_acc + slot0 * (kHeads * kHeadDim / 4) + p;
 
+    // One pass with a running reference exponent: a batch's (m, l) pairs and accumulator pieces are loaded
+    // together, so the weights do not wait for a first round trip that only fetches the maxima.
     float m = -INFINITY;
-    for (int s0 = 0; s0 < n_valid; s0 += 4) {
-        float mm[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int s = s0 + u < n_valid ? s0 + u : n_valid - 1;
-            mm[u] = ml_base[(size_t)s * slot_step * kHeads].x;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) m = fmaxf(m, mm[u]);
-    }
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
     float l = 0.f;
     for (int s0 = 0; s0 < n_valid; s0 += 4) {
@@ -426,12 +418,20 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
             ml[u] = ml_base[(size_t)s * slot_step * kHeads];
             v[u] = acc_base[(size_t)s * slot_step * (kHeads * kHeadDim / 4)];
         }
+        float m_new = m;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) m_new = fmaxf(m_new, ml[u].x);   // (a repeated last piece changes nothing)
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;       // pieces without tokens have m = -inf
+        const float keep = fast_exp2(m - m_safe);                    // 0 while nothing has been summed
+        sum.x *= keep; sum.y *= keep; sum.z *= keep; sum.w *= keep;
+        l *= keep;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float w = s0 + u < n_valid ? fast_exp2(ml[u].x - m) : 0.f;     // a piece without tokens has m = -inf: weight 0
+            const float w = s0 + u < n_valid ? fast_exp2(ml[u].x - m_safe) : 0.f;
             sum.x += w * v[u].x; sum.y += w * v[u].y; sum.z += w * v[u].z; sum.w += w * v[u].w;
             l += w * ml[u].y;
         }
+        m = m_new;
     }
     const float inv = 1.0f / l;
     *o = make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
