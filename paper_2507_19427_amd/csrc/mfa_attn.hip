@@ -69,70 +69,83 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     const int n = lane & 15;
     const int g = lane >> 4;
 
-    Schedule sched = schedule_begin(a, lds_base);
-    Segment r;
-    bool first_segment = true;
-    while (schedule_next(a, lds_base, sched, r)) {
-        if (!first_segment) __syncthreads();          // the previous segment's exchange area is the tile memory
-        first_segment = false;
+    // Wave w brings rows [8w, 8w+8) of a tile's K and V: all in unit w/4.  Rows at or past the segment's
+    // end re-read its last valid token, so nothing outside the sequence is touched and every LDS row
+    // holds finite data (the weights of those rows are masked to zero).
+    auto issue_tile = [&](const Segment& sg, int tile, int slot, int page) {
+        const int tile_t0 = sg.t0 + tile * kTile;
+        const int64_t row0 = tile_row0<PAGED>(a, sg.b, tile_t0, page);
+        const unsigned char* k_tile = (const unsigned char*)a.k + row0 * 512;   // wave-uniform: scalar registers
+        const unsigned char* v_tile = (const unsigned char*)a.v + row0 * 512;
+        const int p16 = lane & 31;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int row = 8 * wave + 2 * u + (lane >> 5);          // row of the tile this lane fills
+            int in_tile = row;
+            if (tile_t0 + row > sg.t1 - 1) in_tile = sg.t1 - 1 - tile_t0;
+            const int key = row & 15;
+            const int ck = p16 ^ key;
+            const int cv = ((((p16 >> 1) ^ key) << 1) | (p16 & 1));
+            const int first_row = 8 * wave + 2 * u;                   // wave-uniform
+            const uint32_t dst = lds_addr0 + slot * kSlotBytes + (first_row >> 5) * kUnitBytes + (first_row & 31) * 512;
+            load_to_lds_16B(k_tile, (uint32_t)(in_tile * 512 + ck * 16), dst);
+            load_to_lds_16B(v_tile, (uint32_t)(in_tile * 512 + cv * 16), dst + kUnitVOffset);
+        }
+    };
+    auto load_q = [&](QFrags<16>& q, const Segment& sg) {
+        load_q_fragments(q.f, a.q, QL == 2 ? a.q_len * sg.b + a.q0 + grp : sg.b, 16 * wq + n, g);
+    };
 
-        QFrags<16> q;
-        load_q_fragments(q.f, a.q, QL == 2 ? a.q_len * r.b + a.q0 + grp : r.b, 16 * wq + n, g);
+    // The workgroup's segments are worked off as one stream of tiles: while the last tile of a segment is
+    // multiplied, the first tile of the next one is already on its way into the other slot,
+    // and the end-of-segment exchange uses the slot of the tile just finished.
+    Schedule sched = schedule_begin(a, lds_base);
+    Segment r, r_next;
+    if (!schedule_next(a, lds_base, sched, r)) return;
+    QFrags<16> q;
+    load_q(q, r);
+    int slot0 = 0;                                    // slot of the segment's first tile
+    issue_tile(r, 0, 0, lookup_page<PAGED>(a, r.b, r.t0));
+    for (bool more = true; more;) {
         const int end_mine = r.len - (a.q_len - 1 - a.q0 - grp);      // QL == 2: grp = query token of the pair
         const int t1_mine = QL == 2 ? (r.t1 < end_mine ? r.t1 : end_mine) : r.t1;
-
-        // Wave w brings rows [8w, 8w+8) of the tile's K and V: all in unit w/4.  Rows at or past t1
-        // re-read the last valid token, so nothing outside the sequence is touched and every LDS row
-        // holds finite data (the weights of those rows are masked to zero).
-        auto issue_tile = [&](int tile, int slot, int page) {
-            const int tile_t0 = r.t0 + tile * kTile;
-            const int64_t row0 = tile_row0<PAGED>(a, r.b, tile_t0, page);
-            const unsigned char* k_tile = (const unsigned char*)a.k + row0 * 512;   // wave-uniform: scalar registers
-            const unsigned char* v_tile = (const unsigned char*)a.v + row0 * 512;
-            const int p16 = lane & 31;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int row = 8 * wave + 2 * u + (lane >> 5);          // row of the tile this lane fills
-                int in_tile = row;
-                if (tile_t0 + row > r.t1 - 1) in_tile = r.t1 - 1 - tile_t0;
-                const int key = row & 15;
-                const int ck = p16 ^ key;
-                const int cv = ((((p16 >> 1) ^ key) << 1) | (p16 & 1));
-                const int first_row = 8 * wave + 2 * u;                   // wave-uniform
-                const uint32_t dst = lds_addr0 + slot * kSlotBytes + (first_row >> 5) * kUnitBytes + (first_row & 31) * 512;
-                load_to_lds_16B(k_tile, (uint32_t)(in_tile * 512 + ck * 16), dst);
-                load_to_lds_16B(v_tile, (uint32_t)(in_tile * 512 + cv * 16), dst + kUnitVOffset);
-            }
-        };
-
         WaveState st;
         init_state(st);
-
-        issue_tile(0, 0, lookup_page<PAGED>(a, r.b, r.t0));
         int page_next = r.n_tiles > 1 ? lookup_page<PAGED>(a, r.b, r.t0 + kTile) : 0;
+        more = false;
         for (int it = 0; it < r.n_tiles; ++it) {
-            const int slot = it & 1;
+            const int slot = (slot0 + it) & 1;
             wait_vmem_all();
             __syncthreads();
             if (it + 1 < r.n_tiles) {
-                issue_tile(it + 1, slot ^ 1, page_next);
+                issue_tile(r, it + 1, slot ^ 1, page_next);
                 if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
+            } else {
+                more = schedule_next(a, lds_base, sched, r_next);
+                if (more) issue_tile(r_next, 0, slot ^ 1, lookup_page<PAGED>(a, r_next.b, r_next.t0));
             }
             if (QL == 2) {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int unit = slot * kSlotBytes + u * kUnitBytes;
                     process_unit<16>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + u * kUnitTokens,
-                                        t1_mine, a.scale_log2e, n, g, 0, 0);
+                                     t1_mine, a.scale_log2e, n, g, 0, 0);
                 }
             } else {
                 const int unit = slot * kSlotBytes + grp * kUnitBytes;
                 process_unit<16>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + grp * kUnitTokens,
-                                    t1_mine, a.scale_log2e, n, g, 0, 0);
+                                 t1_mine, a.scale_log2e, n, g, 0, 0);
             }
         }
+        const int last_slot = (slot0 + r.n_tiles - 1) & 1;
+        if (more) load_q(q, r_next);                  // ordinary loads (kept out of the tile loop, where the compiler's
+                                                      // waits for them would also wait for the tile in flight)
         if (QL == 2) finish_segment_two(st, a, r, grp, wq, lane);
-        else         finish_segment(st, lds_base, a, r, wq, grp, lane);
+        else         finish_segment(st, lds_base, last_slot * kSlotBytes, a, r, wq, grp, lane);
+        if (more) {
+            r = r_next;
+            slot0 = last_slot ^ 1;
+        }
     }
 }
 
@@ -359,7 +372,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
         }
         drain_tiles<BITS>(regs[0], regs[1]);  // the repeats of the last tile issued past the end
         if (QL == 2) finish_segment_two(st, a, r, grp, wq, lane);
-        else         finish_segment(st, lds_base, a, r, wq, grp, lane);
+        else         finish_segment(st, lds_base, 0, a, r, wq, grp, lane);
     }
 }
 

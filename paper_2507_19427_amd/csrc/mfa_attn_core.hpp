@@ -339,27 +339,30 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& 
 }
 
 // After the last tile the two waves that share 16 heads (grp 0 and 1: the two token halves of
-// every tile) exchange halves of their accumulators through LDS (the tile buffers are dead by
-// then; the caller guarantees no direct load is in flight): grp 0 finishes output blocks 0..7,
+// every tile) exchange halves of their accumulators through 64 KB of LDS at xbase (a tile buffer
+// that is dead by then; the caller guarantees that no direct load into it is in flight) and a
+// spare KB behind the tile memory: grp 0 finishes output blocks 0..7,
 // grp 1 blocks 8..15, so all eight waves merge and store in parallel.  One split: the final
 // result goes to `out`.  Several splits: the unnormalised partial goes to the workspace in
 // lane order (float4 index (wq*16 + db)*64 + lane, fully coalesced), with (m, l) per head.
 template <int KEEP, int SEND>
-__device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, int b, int slot,
+__device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, int xbase, const AttnArgs& a, int b, int slot,
                                             bool final_result, int wq, int grp, int lane)
 {
     const int n = lane & 15, g = lane >> 4;
     const int head = 16 * wq + n;
-    const int mine = (wq * 2 + grp) * 8;              // my 8 KB exchange slots (1 KB each)
+    const int mine = (wq * 2 + grp) * 8;              // my 8 KB exchange slots (1 KB each), from xbase on
     const int theirs = (wq * 2 + (grp ^ 1)) * 8;
-    constexpr int kMlOff = 65536;                     // (m, l) exchange area after the 64 KB of blocks
+    constexpr int kMlOff = 2 * 2 * kUnitBytes;        // (m, l) per head and wave: the spare KB behind the tile memory
 #pragma unroll
-    for (int i = 0; i < 8; ++i) *LDS_AT(f32x4, lds_base, (mine + i) * 1024 + lane * 16) = st.acc[SEND + i];
-    *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + grp) * 2 + 0) * 256 + lane * 4) = st.m;
-    *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + grp) * 2 + 1) * 256 + lane * 4) = st.l;
+    for (int i = 0; i < 8; ++i) *LDS_AT(f32x4, lds_base, xbase + (mine + i) * 1024 + lane * 16) = st.acc[SEND + i];
+    if (g == 0) {                                     // m and (after head_sum) l are equal in the four lanes of a head
+        *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + grp) * 2 + 0) * 64 + n * 4) = st.m;
+        *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + grp) * 2 + 1) * 64 + n * 4) = st.l;
+    }
     __syncthreads();
-    const float m_o = *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + (grp ^ 1)) * 2 + 0) * 256 + lane * 4);
-    const float l_o = *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + (grp ^ 1)) * 2 + 1) * 256 + lane * 4);
+    const float m_o = *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + (grp ^ 1)) * 2 + 0) * 64 + n * 4);
+    const float l_o = *LDS_AT(float, lds_base, kMlOff + ((wq * 2 + (grp ^ 1)) * 2 + 1) * 64 + n * 4);
     const float m = fmaxf(st.m, m_o);                 // finite: the segment has a token, seen by grp 0
     const float w_s = fast_exp2(st.m - m);
     const float w_o = fast_exp2(m_o - m);
@@ -369,7 +372,7 @@ __device__ __forceinline__ void finish_half(WaveState& st, lds_ptr_t lds_base, c
     f32x4* part = (f32x4*)a.ws_acc + (size_t)slot * (kHeads * kHeadDim / 4) + (size_t)wq * 16 * 64 + lane;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const f32x4 other = *LDS_AT(f32x4, lds_base, (theirs + i) * 1024 + lane * 16);
+        const f32x4 other = *LDS_AT(f32x4, lds_base, xbase + (theirs + i) * 1024 + lane * 16);
         const f32x4 r = st.acc[KEEP + i] * w_s + other * w_o;
         if (final_result) *(f32x4*)(o + 16 * (KEEP + i)) = r * inv;
         else part[(KEEP + i) * 64] = r;
@@ -398,13 +401,14 @@ __device__ __forceinline__ void make_uniform(Segment& r)
     r.final_result = __builtin_amdgcn_readfirstlane((int)r.final_result) != 0;
 }
 
-__device__ __forceinline__ void finish_segment(WaveState& st, lds_ptr_t lds_base, const AttnArgs& a, const Segment& r,
+// xbase: LDS byte offset of the 64 KB the exchange may use (tile memory nobody reads any more).
+__device__ __forceinline__ void finish_segment(WaveState& st, lds_ptr_t lds_base, int xbase, const AttnArgs& a, const Segment& r,
                                                int wq, int grp, int lane)
 {
     st.l = head_sum(st.l);
     __syncthreads();                                  // every wave is done reading the tile buffers
-    if (grp == 0) finish_half<0, 8>(st, lds_base, a, r.b, r.slot, r.final_result, wq, grp, lane);
-    else          finish_half<8, 0>(st, lds_base, a, r.b, r.slot, r.final_result, wq, grp, lane);
+    if (grp == 0) finish_half<0, 8>(st, lds_base, xbase, a, r.b, r.slot, r.final_result, wq, grp, lane);
+    else          finish_half<8, 0>(st, lds_base, xbase, a, r.b, r.slot, r.final_result, wq, grp, lane);
 }
 
 // Two query tokens per sequence (the wave layout is then 2 query tokens x 4 head groups, and every wave
