@@ -61,3 +61,21 @@ def test_config4_b16_ctx32768():
     assert np.isfinite(got).all()
     _check_sampled(case, got, 32, U.TOL_BF16)
     _check_convex(lambda b, L: case.v[b, :L].float().numpy(), case.seq_lens, got)
+
+
+def test_two_very_long_sequences():
+    """131,072 tokens per sequence (four times the longest named context): one sequence is cut over 128
+    workgroups, 2048 tiles in all; sampled rows against the oracle, bf16 and fp8."""
+    print("\n[case] B=2 ctx=131072", flush=True)
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=2, max_seq_len=131072))
+    for kv_dtype, tol in (("bf16", U.TOL_BF16), ("fp8", U.TOL_FP8)):
+        case = W.make_contiguous_case("verylong", 61, B=2, S=131072, seq_lens=[131072, 100001], kv_dtype=kv_dtype, poison=True)
+        got = U.run_gpu(ctx, case, hint=131072)
+        assert np.isfinite(got).all()
+        rows = [(0, 0), (0, 63), (1, 17), (1, 40), (0, 31), (1, 5)]
+        ref = U.run_oracle(case, rows=rows)
+        sub = np.stack([got[b, h] for b, h in rows])
+        err = U.row_normalised_error(sub, ref)
+        print(f"   {kv_dtype}: row-normalised max error on {len(rows)} sampled rows {err:.3e}", flush=True)
+        assert err <= tol
+    ctx.close()
