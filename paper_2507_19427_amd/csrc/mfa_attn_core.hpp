@@ -316,17 +316,28 @@ __device__ __forceinline__ void pv_unit(WaveState& st, lds_ptr_t lds_base, int v
 {
     const int v_row = 4 * g + (n >> 2);                 // V: row within a 16-token block (= swizzle key)
     const int v_lane_off = v_row * (PADDED ? kPaddedVRow : 512) + ((n & 3) << 3);
-#pragma unroll
-    for (int db = 0; db < 16; ++db) {
-        union { bf16x8 v; s16x4 h[2]; } vf;
+    union VFrag { bf16x8 v; s16x4 h[2]; };
+    auto read_v = [&](VFrag& f, int db) {
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
             const int off = PADDED ? vbase + tb * 16 * kPaddedVRow + v_lane_off + (db << 5)
                                    : vbase + tb * 8192 + v_lane_off + ((db ^ v_row) << 5);
-            vf.h[tb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
+            f.h[tb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
         }
-        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf, st.acc[db], 0, 0, 0);
+    };
+    // The operands of kAhead output blocks are on their way while one block is multiplied: an LDS read takes
+    // several times as long as the MFMA it feeds, and a wave has only one other wave on its SIMD to hide it.
+    constexpr int kAhead = PADDED ? 4 : 2;
+    VFrag f[kAhead];
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) read_v(f[i], i);
+#pragma unroll
+    for (int db = 0; db < 16; ++db) {
+        __builtin_amdgcn_sched_barrier(0);
+        st.acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[db % kAhead].v, pf, st.acc[db], 0, 0, 0);
+        if (db + kAhead < 16) read_v(f[db % kAhead], db + kAhead);
     }
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int BITS>
