@@ -352,17 +352,26 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
             constexpr int P = decltype(parity_c)::value;                    // t & 1
             wait_all_but_youngest_step<BITS>(regs[P ^ 1]);       // registers of tile t+1 and keys of tile t have landed
             __syncthreads();                               // ... for every wave; everyone is done with tile t-1
+            const int kb = kLbKBase + kslot * kLbKSlotBytes;
+            const int vb = P * kLbVImageBytes;
+            const int scales = kLbScaleBase + P * 512;
+            // The score products of this wave's (first) unit are issued ahead of the conversion of the next tile's
+            // values: the MFMA pipe and the LDS work while the vector ALU converts (4 % on the 8-bit workload,
+            // compared on one box).
+            const int u0 = QL == 2 ? 0 : grp;
+            const RawScores raw0 = qk_unit<BITS>(q, lds_base, kb + u0 * kUnitTokens * kRowBytes, n, g);
             store_tile(regs[P ^ 1], P ^ 1);                                 // values of tile t+1
             load_tile(regs[P ^ 1], t + 3);
             issue_keys(t + 2, kslot == 0 ? 2 : kslot - 1);                  // (t + 2) % 3, the slot tile t-1 has left
-            auto unit = [&](int u) {
-                const int scales = kLbScaleBase + P * 512 + u * kUnitTokens * 4;
-                process_unit<BITS>(st, q, lds_base, kLbKBase + kslot * kLbKSlotBytes + u * kUnitTokens * kRowBytes,
-                                   P * kLbVImageBytes + u * kPaddedVUnitBytes, r.t0 + t * kTile + u * kUnitTokens, t1_mine,
-                                   a.scale_log2e, n, g, scales, scales + 256);
-            };
-            if (QL == 2) { unit(0); unit(1); }
-            else         unit(grp);
+            {
+                const bf16x8 pf = softmax_unit<BITS>(st, q, raw0, lds_base, r.t0 + t * kTile + u0 * kUnitTokens, t1_mine,
+                                                     a.scale_log2e, g, scales + u0 * kUnitTokens * 4, scales + 256 + u0 * kUnitTokens * 4);
+                pv_unit<true>(st, lds_base, vb + u0 * kPaddedVUnitBytes, pf, n, g);
+            }
+            if (QL == 2)
+                process_unit<BITS>(st, q, lds_base, kb + kUnitTokens * kRowBytes, vb + kPaddedVUnitBytes,
+                                   r.t0 + t * kTile + kUnitTokens, t1_mine, a.scale_log2e, n, g,
+                                   scales + kUnitTokens * 4, scales + 256 + kUnitTokens * 4);
             kslot = kslot == 2 ? 0 : kslot + 1;
         };
         for (int t = 0; t < r.n_tiles; t += 2) {

@@ -174,15 +174,11 @@ __device__ __forceinline__ void load_split_q(QFrags<BITS>& q, const void* qptr, 
 //   unit_t0    index (within the sequence) of the unit's first token; tokens >= t1 are masked
 //   8 / 4 bit  kscale/vscale point (LDS byte offsets) at the fp32 per-token scales of the unit's 32 tokens
 //
-// First half of a unit: scores, online softmax, rescale of what has been accumulated so far.  Returns
-// the unit's attention weights as the B operand of the weighted sum (8 tokens of this lane's head).
+// Raw scores of a unit (2 blocks of 16 tokens), before any scale: q . k for this lane's head and its 8 tokens.
+struct RawScores { f32x4 s[2]; };
 template <int BITS>
-__device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& q, lds_ptr_t lds_base, int kbase,
-                                             int unit_t0, int t1, float scale_log2e, int n, int g,
-                                             int kscale_off, int vscale_off)
+__device__ __forceinline__ RawScores qk_unit(const QFrags<BITS>& q, lds_ptr_t lds_base, int kbase, int n, int g)
 {
-    // ---- scores for 2 blocks of 16 tokens
-    constexpr bool FP8 = BITS != 16;                     // 8-bit arithmetic on the scores, scales beside the codes
     f32x4 s[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
     if constexpr (BITS == 4) {
         // e2m1 keys x e4m3 query terms with unit block scales (E8M0 exponent 127)
@@ -200,7 +196,6 @@ __device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& 
                 s[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf, q.hi[c], s[tb], 4, 0, 0, kOne, 0, kOne);
             }
         }
-        scale_log2e *= q.inv_scale;
     } else if constexpr (BITS == 8) {
         // e4m3 x e4m3 with unit block scales (E8M0 exponent 127)
         constexpr int kOne = 0x7F7F7F7F;
@@ -217,7 +212,6 @@ __device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& 
                 s[tb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kf.v, q.hi[c], s[tb], 0, 0, 0, kOne, 0, kOne);
             }
         }
-        scale_log2e *= q.inv_scale;
     } else {
         const int k_lane_off = n * 512;                 // K: row n of a 16-token block, swizzle key n
 #pragma unroll
@@ -230,6 +224,20 @@ __device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& 
             }
         }
     }
+    RawScores r;
+    r.s[0] = s[0];
+    r.s[1] = s[1];
+    return r;
+}
+// Online softmax of a unit from its raw scores, and the rescale of what has been accumulated so far.
+// Returns the unit's attention weights as the B operand of the weighted sum (8 tokens of this lane's head).
+template <int BITS>
+__device__ __forceinline__ bf16x8 softmax_unit(WaveState& st, const QFrags<BITS>& q, const RawScores& raw, lds_ptr_t lds_base,
+                                               int unit_t0, int t1, float scale_log2e, int g, int kscale_off, int vscale_off)
+{
+    constexpr bool FP8 = BITS != 16;                     // 8-bit arithmetic on the scores, scales beside the codes
+    f32x4 s[2] = {raw.s[0], raw.s[1]};
+    if constexpr (FP8) scale_log2e *= q.inv_scale;
     f32x4 vsc[2];
     if (FP8) {
 #pragma unroll
@@ -301,6 +309,16 @@ __device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& 
         for (int db = 0; db < 16; ++db) st.acc[db] *= alpha;
     }
     return pf;
+}
+
+// Scores and softmax of a unit in one go.
+template <int BITS>
+__device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& q, lds_ptr_t lds_base, int kbase,
+                                             int unit_t0, int t1, float scale_log2e, int n, int g,
+                                             int kscale_off, int vscale_off)
+{
+    const RawScores raw = qk_unit<BITS>(q, lds_base, kbase, n, g);
+    return softmax_unit<BITS>(st, q, raw, lds_base, unit_t0, t1, scale_log2e, g, kscale_off, vscale_off);
 }
 
 // Second half of a unit: O^T += V^T P^T over the unit's 32 tokens.
