@@ -258,6 +258,26 @@ MFA_API mfa_status mfa_decode_attn_paged_multi(mfa_ctx* ctx, const void* q, cons
                                        float* out, void* hip_stream);
 
 /*
+ * mfa_decode_attn for callers that cannot allocate device memory or hand over a
+ * workspace at the time of the call: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation.  Same arguments, same kernels and the
+ * same (bitwise) result as mfa_decode_attn, but the partial results of the context
+ * splits go to a fixed device array inside the library (about 25.4 MB per device,
+ * held from the time the library is loaded until the process ends) instead of the
+ * context's workspace; the call itself allocates nothing and calls no allocating
+ * routine.  Limits: B <= 128 and B + workgroups <= 384 partial-result slots
+ * (always true for B <= 128 with the default 256 workgroups); beyond them the call
+ * returns MFA_ERR_WORKSPACE_TOO_SMALL and launches nothing.  All calls on one
+ * device share that one array, whichever context they go through: calls that
+ * overlap on a device (different streams without ordering) race; order them on
+ * one stream.  Nothing in the array has to survive from call to call.
+ */
+MFA_API mfa_status mfa_decode_attn_static(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                                  const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
+                                  int64_t kv_seq_stride_tokens, const int32_t* seq_lens,
+                                  int32_t max_seq_len_hint, int32_t B, float* out, void* hip_stream);
+
+/*
  * Measurement aid, not part of the serving path: while both handles are non-NULL
  * (hipEvent_t passed as void*, created by the caller with timing enabled), every
  * mfa_decode_attn / mfa_decode_attn_paged call on this context attaches the two

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     mfa_decode_workspace_bytes, mfa_decode_init, mfa_decode_num_splits, mfa_query_proj,
     mfa_decode_attn, mfa_decode_attn_paged, mfa_debug_gather_paged, mfa_debug_set_kernel_events, mfa_debug_stream_read,
     mfa_kv_append, mfa_kv_append_paged, mfa_debug_kv_record, mfa_out_proj,
-    mfa_decode_attn_multi, mfa_decode_attn_paged_multi,
+    mfa_decode_attn_multi, mfa_decode_attn_paged_multi, mfa_decode_attn_static,
     PreparedDecodeAttn,
 )

@@ -28,7 +28,7 @@ EXPORTS = [
     "mfa_query_proj", "mfa_decode_attn", "mfa_decode_attn_paged", "mfa_debug_gather_paged",
     "mfa_decode_num_splits", "mfa_debug_set_kernel_events", "mfa_debug_stream_read",
     "mfa_kv_append", "mfa_kv_append_paged", "mfa_debug_kv_record", "mfa_out_proj",
-    "mfa_decode_attn_multi", "mfa_decode_attn_paged_multi",
+    "mfa_decode_attn_multi", "mfa_decode_attn_paged_multi", "mfa_decode_attn_static",
 ]
 
 
@@ -89,6 +89,8 @@ def lib():
     L.mfa_query_proj.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp]
     L.mfa_decode_attn.restype = ctypes.c_int
     L.mfa_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i64, vp, i32, i32, vp, vp]
+    L.mfa_decode_attn_static.restype = ctypes.c_int
+    L.mfa_decode_attn_static.argtypes = L.mfa_decode_attn.argtypes
     L.mfa_decode_attn_paged.restype = ctypes.c_int
     L.mfa_decode_attn_paged.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int, i32, vp, i32, vp, i32, i32, vp, vp]
     L.mfa_decode_attn_multi.restype = ctypes.c_int
@@ -220,7 +222,7 @@ def mfa_query_proj(ctx: MfaContext, x, w_qa, w_qb, rms_gain=None, q_out=None):
 
 
 def mfa_decode_attn(ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_hint, k_scale=None,
-                    v_scale=None, out=None):
+                    v_scale=None, out=None, _entry="mfa_decode_attn"):
     """q bf16 [B,H,D]; k_cache,v_cache [B,S,D] bf16 or float8_e4m3fn; seq_lens int32 [B] on device."""
     cfg = ctx.cfg
     _want(q, torch.bfloat16, "q")
@@ -243,10 +245,21 @@ def mfa_decode_attn(ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_
         out = torch.empty(B, cfg.n_q_heads, cfg.head_dim, dtype=torch.float32, device=q.device)
     else:
         _want(out, torch.float32, "out")
-    _check(lib().mfa_decode_attn(ctx.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
-                                 kvd, S, _ptr(seq_lens), int(max_seq_len_hint), B, _ptr(out), _stream()),
-           "mfa_decode_attn")
+        if tuple(out.shape) != (B, cfg.n_q_heads, cfg.head_dim):
+            raise ValueError("out shape")
+    _check(getattr(lib(), _entry)(ctx.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
+                                  kvd, S, _ptr(seq_lens), int(max_seq_len_hint), B, _ptr(out), _stream()), _entry)
     return out
+
+
+def mfa_decode_attn_static(ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_hint, out, k_scale=None,
+                           v_scale=None):
+    """mfa_decode_attn with the partial results in the library's fixed device array instead of the context's
+    workspace (for callers that cannot allocate); `out` is the caller's, nothing is allocated here either."""
+    if out is None:
+        raise ValueError("mfa_decode_attn_static writes into the caller's `out`")
+    return mfa_decode_attn(ctx, q, k_cache, v_cache, seq_lens, max_seq_len_hint, k_scale=k_scale, v_scale=v_scale,
+                           out=out, _entry="mfa_decode_attn_static")
 
 
 def mfa_decode_attn_paged(ctx: MfaContext, q, k_pool, v_pool, block_table, seq_lens, max_seq_len_hint,
@@ -274,6 +287,8 @@ def mfa_decode_attn_paged(ctx: MfaContext, q, k_pool, v_pool, block_table, seq_l
         out = torch.empty(B, cfg.n_q_heads, cfg.head_dim, dtype=torch.float32, device=q.device)
     else:
         _want(out, torch.float32, "out")
+        if tuple(out.shape) != (B, cfg.n_q_heads, cfg.head_dim):
+            raise ValueError("out shape")
     _check(lib().mfa_decode_attn_paged(ctx.handle, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale_pool),
                                        _ptr(v_scale_pool), kvd, n_pages, _ptr(block_table), block_table.shape[1],
                                        _ptr(seq_lens), int(max_seq_len_hint), B, _ptr(out), _stream()),

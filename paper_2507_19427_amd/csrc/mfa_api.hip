@@ -2,6 +2,7 @@
 // Every entry point is declared and documented in include/mfa.h.
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -23,11 +24,48 @@ struct mfa_ctx {
     int32_t qproj_rows_pad;
     hipEvent_t ev_before;      // measurement aid: recorded around the streaming kernel when both are set
     hipEvent_t ev_after;
+    unsigned char* static_scratch;   // this device's copy of the file-scope scratch array (mfa_decode_attn_static)
 };
 
 namespace {
 
 constexpr int32_t kDefaultTargetItems = 256;   // MI355X has 256 compute units; one workgroup fills one
+
+// ---- Scratch of mfa_decode_attn_static, the attention call for callers that cannot allocate or
+// pass a workspace: the partial results (acc, then (m, l)) of at most kStaticSlots segments and the
+// per-sequence merge records of at most kStaticMaxBatch sequences live in a file-scope device array.
+// Every device the library runs on holds its own copy from the time the code object is loaded until
+// the process ends; its address on a device is asked for once, in mfa_decode_init with that device
+// current, and only that address (never the array's name) is used in host code.
+constexpr int32_t kStaticMaxBatch = 128;
+constexpr size_t kStaticSlots = (size_t)kStaticMaxBatch + kDefaultTargetItems;
+constexpr size_t kStaticAccOffset = 0;
+constexpr size_t kStaticMlOffset = kStaticAccOffset + kStaticSlots * kPartialAccFloats * sizeof(float);
+constexpr size_t kStaticSegOffset = kStaticMlOffset + kStaticSlots * kPartialMlFloats * sizeof(float);
+constexpr size_t kStaticScratchBytes = kStaticSegOffset + (size_t)kStaticMaxBatch * 2 * sizeof(int32_t);
+static_assert(kStaticMlOffset % 256 == 0 && kStaticSegOffset % 256 == 0, "the pieces of the scratch array stay 256-byte aligned");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices];        // per device; filled with that device current
+
+// The calling thread's current device must be `device`.
+hipError_t static_scratch_for_device(int device, unsigned char** out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 int32_t target_items_from_env()
 {
@@ -172,6 +210,8 @@ mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t work
     if (prev != cfg->device && hipSetDevice(cfg->device) != hipSuccess) return MFA_ERR_HIP;
     hipError_t e = prepare_decode_attn_kernels();
     if (e == hipSuccess) e = prepare_query_proj_kernels();
+    unsigned char* static_scratch = nullptr;
+    if (e == hipSuccess) e = static_scratch_for_device(cfg->device, &static_scratch);
     if (prev != cfg->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) return MFA_ERR_HIP;
 
@@ -194,6 +234,7 @@ mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t work
     ctx->qproj_rows_pad = w.rows_pad;
     ctx->ev_before = nullptr;
     ctx->ev_after = nullptr;
+    ctx->static_scratch = static_scratch;
     *out_ctx = ctx;
     return MFA_OK;
 }
@@ -373,6 +414,32 @@ mfa_status mfa_decode_attn(mfa_ctx* ctx, const void* q, const void* k_cache, con
 {
     return mfa_decode_attn_multi(ctx, q, k_cache, v_cache, k_scale, v_scale, kv_dtype, kv_seq_stride_tokens, seq_lens,
                                  max_seq_len_hint, B, 1, out, hip_stream);
+}
+
+mfa_status mfa_decode_attn_static(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,
+                                  const float* k_scale, const float* v_scale, mfa_kv_dtype kv_dtype,
+                                  int64_t kv_seq_stride_tokens, const int32_t* seq_lens, int32_t max_seq_len_hint,
+                                  int32_t B, float* out, void* hip_stream)
+{
+    const mfa_status st = check_attn_common(ctx, q, k_cache, v_cache, k_scale, v_scale, kv_dtype, seq_lens,
+                                            max_seq_len_hint, B, out);
+    if (st != MFA_OK) return st;
+    if (kv_seq_stride_tokens < max_seq_len_hint) return MFA_ERR_INVALID_ARG;
+    if (!ctx->static_scratch) return MFA_ERR_HIP;
+    AttnArgs a{};
+    a.q = q; a.k = k_cache; a.v = v_cache; a.k_scale = k_scale; a.v_scale = v_scale;
+    a.seq_lens = seq_lens; a.block_table = nullptr; a.out = out;
+    a.seq_stride_tokens = kv_seq_stride_tokens; a.max_blocks_per_seq = 0;
+    fill_common(ctx, a, B, max_seq_len_hint);
+    // the partial results of this call fit the fixed array, or the call is refused before any launch
+    const size_t slots = a.n_wgs > 0 ? balanced_slots(B, a.n_wgs) : (size_t)B * a.n_splits;
+    if (B > kStaticMaxBatch || slots > kStaticSlots) return MFA_ERR_WORKSPACE_TOO_SMALL;
+    a.ws_acc = reinterpret_cast<float*>(ctx->static_scratch + kStaticAccOffset);
+    a.ws_ml = reinterpret_cast<float*>(ctx->static_scratch + kStaticMlOffset);
+    a.ws_seg = reinterpret_cast<int32_t*>(ctx->static_scratch + kStaticSegOffset);
+    const hipError_t e = launch_decode_attn(a, kv_dtype, static_cast<hipStream_t>(hip_stream), nullptr, nullptr);
+    if (e == hipErrorNotSupported) return MFA_ERR_UNSUPPORTED;
+    return e == hipSuccess ? MFA_OK : MFA_ERR_HIP;
 }
 
 mfa_status mfa_decode_attn_paged_multi(mfa_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
