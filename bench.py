@@ -14,8 +14,11 @@ cache, the whole attention layer at the paper's 8K / 32K contexts); they exist s
 those shapes can be taken with this same program; cfg2q2 / fp8q2 run the step with two query tokens per
 sequence, fp4 / fp4q2 the 4-bit cache.
 
-Prints ONE JSON line: metric/value = KV tokens per second, plus
-  roofline      HBM roofline of the streaming attention kernel from HIP-event timings taken in the timed region
+Prints ONE JSON line: metric/value = KV tokens per second (from the wall time of exactly --steps steps), plus
+  roofline      HBM roofline of the streaming attention kernel (`frac`: HIP events attached to that kernel's
+                dispatch) and of the whole attention call (`frac_whole_call`: streaming kernel + merge kernel +
+                the gap between them, HIP events around the call on its stream), each from EVENT_SAMPLES
+                samples taken in a pass of their own right after the timed steps, whatever --steps is
   cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample of the same workload
 """
 import argparse
@@ -28,16 +31,19 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published peak
-# HBM bytes per launch of the streaming kernel on the default workload, from rocprofv3 --pmc FETCH_SIZE
-# and WRITE_SIZE scaled by what the same counters read for a 256 MiB device copy
-# (profiles/decode_attn_cfg2_b64_ctx4096_hbm_traffic.md): 277.07 MB read + 16.91 MB written.
-MEASURED_TRAFFIC_BYTES = {"cfg2": 135287 * 2.000 * 1024 + 16513 * 1.000 * 1024,
-                          # profiles/decode_attn_other_workloads_hbm_traffic.md
-                          "cfg4": 264310 * 2.000 * 1024 + 16512 * 1024, "cfg5": 270502 * 2.000 * 1024 + 16516 * 1024,
-                          "fp4": 139425 * 2.000 * 1024 + 16516 * 1024, "cfg2q2": 139380 * 2.000 * 1024 + 33025 * 1024}
+# HBM bytes per launch of the streaming kernel, NOT measured in this run: rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for a 256 MiB device copy, as
+# recorded in the named file under profiles/ (which gives the command and the library it was taken on).
+PROFILED_TRAFFIC = {
+    "cfg2": (135287 * 2.000 * 1024 + 16513 * 1.000 * 1024, "profiles/decode_attn_cfg2_b64_ctx4096_hbm_traffic.md"),
+    "cfg4": (264310 * 2.000 * 1024 + 16512 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+    "cfg5": (270502 * 2.000 * 1024 + 16516 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+    "fp4": (139425 * 2.000 * 1024 + 16516 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+    "cfg2q2": (139380 * 2.000 * 1024 + 33025 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+}
 Q_BYTES_PER_SEQ = 64 * 256 * 2
 OUT_BYTES_PER_SEQ = 64 * 256 * 4
-EVENT_STRIDE = 8                       # every 8th timed step carries the kernel's timing events
+EVENT_SAMPLES = 64                     # kernel-only and whole-call event samples, whatever --steps is
 STREAM_READ_GRANULE = 2048 * 8192      # the plain-read probe takes multiples of this many bytes per buffer
 
 
@@ -52,7 +58,9 @@ class Workload:
         self.B = 0
         self.q_len = 1
         self.extra_config = {}
-        self.case = None           # host case for the oracle sample (contiguous bf16 only)
+        self.case = None           # host case for the oracle sample
+        self.attn_calls = []       # per buffer set: the attention call alone (equal to steps when the step is only that)
+        self.attn_only = False
         self.keep = []
 
 
@@ -83,6 +91,7 @@ def build_workload(key, mfa, W, n_sets):
         w.metric = "KV tokens/s, MFA decode attention, B=%d, ctx %d, bf16, 1 GPU" % (B, S)
         w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<false, 1>", 1024
         w.T, w.B, w.case = case.kv_tokens, B, case
+        w.attn_calls, w.attn_only = w.steps, True
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S)}
     elif key == "cfg3":
         case = W.config3_ragged_paged(poison=False)
@@ -99,7 +108,8 @@ def build_workload(key, mfa, W, n_sets):
                   "bf16 KV")
         w.metric = "KV tokens/s, MFA decode attention, B=128, ragged paged ctx 1K-8K, bf16, 1 GPU"
         w.dtype, w.kernel, w.kv_bytes_per_token = "bf16", "mfa::decode_bf16_kernel<true, 1>", 1024
-        w.T, w.B = case.kv_tokens, B
+        w.T, w.B, w.case = case.kv_tokens, B, case
+        w.attn_calls, w.attn_only = w.steps, True
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S), "max_ctx": S}
     elif key == "cfg5":
         qc = W.config5_query()
@@ -125,7 +135,8 @@ def build_workload(key, mfa, W, n_sets):
                   "fp8 e4m3 KV with per-token fp32 scales")
         w.metric = "KV tokens/s, MFA query path + decode attention, B=128, ctx 8192, fp8 KV, 1 GPU"
         w.dtype, w.kernel, w.kv_bytes_per_token = "bf16 (fp8 e4m3 KV storage)", "mfa::decode_lowbit_kernel<false, 1, 8>", 520
-        w.T, w.B = case.kv_tokens, B
+        w.T, w.B, w.case = case.kv_tokens, B, case
+        w.attn_calls = attn
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S)}
         w.keep = [x, w_qa, w_qb]
     elif key in ("fp4", "fp4q2"):
@@ -151,6 +162,9 @@ def build_workload(key, mfa, W, n_sets):
         w.kernel = "mfa::decode_lowbit_kernel<false, %d, 4>" % q_len
         w.kv_bytes_per_token = 264
         w.T, w.B, w.q_len = case.kv_tokens, B, q_len
+        w.attn_calls, w.attn_only = w.steps, True
+        if q_len == 1:
+            w.case = case
         w.extra_config = {"query_tokens_per_sequence": q_len}
     elif key in ("cfg2q2", "fp8q2"):
         # Two new tokens per sequence in one pass over the cache (the multi-token step of Section 5.2):
@@ -176,6 +190,7 @@ def build_workload(key, mfa, W, n_sets):
         w.kernel = "mfa::decode_lowbit_kernel<false, 2, 8>" if fp8 else "mfa::decode_bf16_kernel<false, 2>"
         w.kv_bytes_per_token = 520 if fp8 else 1024
         w.T, w.B, w.q_len = case.kv_tokens, B, 2
+        w.attn_calls, w.attn_only = w.steps, True
         w.extra_config = {"query_tokens_per_sequence": 2}
     elif key in ("layer8k", "layer32k", "layer8k_fp8", "layer32k_fp8"):
         # One whole attention layer of a decode step, the unit of the paper's attention-latency table
@@ -224,6 +239,7 @@ def build_workload(key, mfa, W, n_sets):
         w.kernel = "mfa::decode_lowbit_kernel<false, 1, 8>" if fp8 else "mfa::decode_bf16_kernel<false, 1>"
         w.kv_bytes_per_token = 520 if fp8 else 1024
         w.T, w.B = B * S, B
+        w.attn_calls = attn
         w.extra_config = {"n_splits": mfa.mfa_decode_num_splits(w.ctx, B, S),
                           "weight_bytes_per_step": 2 * (qc.w_qa.numel() + qc.w_qb.numel() + w_kv.numel() + w_o.numel()),
                           "paper_layer_time_us": {"ctx": S, "H800": 281 if S == 8192 else 791, "H20": 438 if S == 8192 else 1452,
@@ -269,31 +285,43 @@ def main():
         w.steps[i % n_sets]()
     torch.cuda.synchronize()
 
-    # HIP events attached by the library to the dispatch of the streaming kernel (on the stream the kernel is
-    # launched on) give the duration of that kernel alone, live in the timed region.  A dispatch that carries
-    # events costs the step about 3.5 us of wall time, so only every EVENT_STRIDE-th step of the timed region
-    # carries them (with K = 200: 25 samples), which keeps their weight in ms_per_step below 0.5 us.
+    # The timed region: exactly K steps, nothing attached to them, barrier-free on one GPU
+    # (synchronize on both sides).
     K = args.steps
-    sampled = list(range(0, K, EVENT_STRIDE))
-    starts = [torch.cuda.Event(enable_timing=True) for _ in sampled]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in sampled]
-    for e in starts + stops:
-        e.record()                                   # materialise the HIP event handles
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        if i % EVENT_STRIDE == 0:
-            mfa.mfa_debug_set_kernel_events(ctx, starts[i // EVENT_STRIDE], stops[i // EVENT_STRIDE])
-        elif i % EVENT_STRIDE == 1:
-            mfa.mfa_debug_set_kernel_events(ctx, None, None)
         w.steps[i % n_sets]()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    mfa.mfa_debug_set_kernel_events(ctx, None, None)
     ms_per_step = (t1 - t0) * 1e3 / K
+
+    # Roofline samples, in a pass of their own right after the timed steps (same buffers, same rotation):
+    # (1) HIP events attached by the library to the dispatch of the streaming kernel, on the stream the kernel
+    #     is launched on: the duration of that kernel alone (a dispatch that carries events costs the step
+    #     about 3.5 us of wall time, which is why the timed steps above carry none);
+    # (2) HIP events recorded on that stream around the whole attention call, i.e. streaming kernel + merge
+    #     kernel + the gap between them: the t of "KV tokens / t" for one call.
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(EVENT_SAMPLES)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(EVENT_SAMPLES)]
+    for e in starts + stops:
+        e.record()                                   # materialise the HIP event handles
+    torch.cuda.synchronize()
+    for i in range(EVENT_SAMPLES):
+        mfa.mfa_debug_set_kernel_events(ctx, starts[i], stops[i])
+        w.steps[i % n_sets]()
+    torch.cuda.synchronize()
+    mfa.mfa_debug_set_kernel_events(ctx, None, None)
     ev_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
     ev_mean = sum(ev_ms) / len(ev_ms)
     ev_median = ev_ms[len(ev_ms) // 2]
+    call_ms = None
+    if w.attn_calls:
+        for i in range(EVENT_SAMPLES):
+            starts[i].record()
+            w.attn_calls[i % n_sets]()
+            stops[i].record()
+        torch.cuda.synchronize()
+        call_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
 
     if args.calibration_copy > 0:
         src = torch.randint(0, 255, (256 << 20,), dtype=torch.uint8, device="cuda")
@@ -305,6 +333,7 @@ def main():
     value = T / (ms_per_step * 1e-3)
     algo_bytes = T * w.kv_bytes_per_token + w.B * w.q_len * (Q_BYTES_PER_SEQ + OUT_BYTES_PER_SEQ)
     achieved = algo_bytes / (ev_mean * 1e-3) / 1e9
+    traffic, traffic_source = PROFILED_TRAFFIC.get(w.key, (None, None))
     roofline = {
         "bound": "hbm",
         "kernel": w.kernel + " (HIP events recorded around it inside the attention call)",
@@ -312,20 +341,35 @@ def main():
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(w.key),
+        "traffic": traffic,
+        "traffic_source": traffic_source and (traffic_source + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a "
+                                              "256 MiB copy; not measured in this run)"),
         "algorithmic_bytes_per_launch": algo_bytes,
         "event_ms_mean": ev_mean,
         "event_ms_median": ev_median,
         "event_ms_min": ev_ms[0],
         "event_samples": len(ev_ms),
     }
+    if call_ms:
+        call_median = call_ms[len(call_ms) // 2]
+        roofline["whole_call"] = {
+            "what": "one attention call = streaming kernel + merge kernel + the gap between them, HIP events "
+                    "around the call on its stream",
+            "ms_median": call_median, "ms_mean": sum(call_ms) / len(call_ms), "ms_min": call_ms[0],
+            "samples": len(call_ms),
+            "kv_tokens_per_s": T / (call_median * 1e-3),
+        }
+        roofline["frac_whole_call"] = algo_bytes / (call_median * 1e-3) / 1e9 / HBM_PEAK_GBS
+    if w.attn_only:
+        # the step is exactly the attention call: the wall time of the timed steps gives the same figure
+        roofline["frac_whole_call_from_ms_per_step"] = algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     # Reference: a do-nothing kernel that only reads the same K and V buffers (plain 16-byte loads), timed
     # the same way.  It bounds what any kernel streaming these bytes can reach on this device.
     if w.read_pairs:
         nbytes = w.read_pairs[0][0].numel() * w.read_pairs[0][0].element_size()
         if nbytes % STREAM_READ_GRANULE == 0:
-            n_ref = min(len(starts), 50)
+            n_ref = min(len(starts), EVENT_SAMPLES)
             for i in range(3):
                 mfa.mfa_debug_stream_read(ctx, *w.read_pairs[i % n_sets])
             torch.cuda.synchronize()
@@ -367,29 +411,49 @@ def main():
 
 
 def cpu_baseline(case, target_seconds):
-    """Time the CPU oracle, as it stands, on the first sequences of the same workload."""
+    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: whole sequences (all 64
+    heads) from the front of the batch, as many as fit the time budget (one (sequence, head) row is the
+    oracle's unit of work; its rows run on all host threads).  Also timed: one sequence on a single thread."""
     from oracle import mfa_oracle as O
     b = O.bits_of
     threads = O.get_threads()
-    S = case.k.shape[1]
+    kd = {"bf16": O.KV_BF16, "fp8": O.KV_E4M3, "fp4": O.KV_E2M1}[case.kv_dtype]
+    opt = lambda t: None if t is None else b(t)
+    lens = case.seq_lens.numpy()
 
     def run(n_seq):
-        sub_lens = case.seq_lens[:n_seq].numpy()
+        rows = [(i, h) for i in range(n_seq) for h in range(64)]
         t0 = time.perf_counter()
-        O.decode_attn(b(case.q[:n_seq]), b(case.k[:n_seq]), b(case.v[:n_seq]), sub_lens, case.scale)
+        if case.paged:
+            O.decode_attn_paged(b(case.q), b(case.k_pool), b(case.v_pool), case.block_table.numpy(), lens, case.scale,
+                                k_scale_pool=opt(case.k_scale_pool), v_scale_pool=opt(case.v_scale_pool), kv_dtype=kd,
+                                rows=rows)
+        else:
+            O.decode_attn(b(case.q), b(case.k), b(case.v), lens, case.scale, k_scale=opt(case.k_scale),
+                          v_scale=opt(case.v_scale), kv_dtype=kd, rows=rows)
         return time.perf_counter() - t0
 
     t1 = run(1)                                        # calibration: one sequence, all 64 heads
-    n = int(max(1, min(case.B, round(target_seconds / max(t1, 1e-3)))))
+    per_token = t1 / max(int(lens[0]), 1)
+    n, tok = 1, int(lens[0])
+    while n < case.B and (tok + int(lens[n])) * per_token <= target_seconds:
+        tok += int(lens[n])
+        n += 1
     t = run(n) if n > 1 else t1
-    tokens = int(case.seq_lens[:n].sum())
+    tokens = int(lens[:n].sum())
+    O.set_threads(1)
+    try:
+        t_single = run(1)
+    finally:
+        O.set_threads(threads)
     return {
         "value": tokens / t,
         "unit": "KV tokens/s",
         "cores": threads,
         "kind": "oracle",
-        "sample": f"first {n} of {case.B} sequences of the same workload (all 64 heads, ctx {S}), "
-                  f"{tokens} KV tokens in {t:.2f} s",
+        "sample": f"first {n} of {case.B} sequences of the same workload (all 64 heads, {tokens} KV tokens) in {t:.2f} s",
+        "single_thread": {"value": int(lens[0]) / t_single, "unit": "KV tokens/s", "cores": 1,
+                          "sample": f"the first sequence (all 64 heads, {int(lens[0])} KV tokens) in {t_single:.2f} s"},
     }
 
 

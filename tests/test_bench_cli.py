@@ -29,5 +29,9 @@ def test_accounting_constants():
     assert bench.Q_BYTES_PER_SEQ == 64 * 256 * 2 and bench.OUT_BYTES_PER_SEQ == 64 * 256 * 4
     # algorithmic bytes of the default workload: 64 x 4096 tokens x 1024 B + 64 x (Q + out)
     assert 64 * 4096 * 1024 + 64 * (bench.Q_BYTES_PER_SEQ + bench.OUT_BYTES_PER_SEQ) == 274726912
-    # measured traffic may exceed the algorithmic bytes by partial results and query re-reads, not by a re-read of the cache
-    assert 1.0 <= bench.MEASURED_TRAFFIC_BYTES["cfg2"] / 274726912 <= 1.15
+    # profiled traffic may exceed the algorithmic bytes by partial results and query re-reads, not by a re-read of
+    # the cache; every figure names the file under profiles/ it was taken from, and that file exists
+    assert 1.0 <= bench.PROFILED_TRAFFIC["cfg2"][0] / 274726912 <= 1.15
+    for _, source in bench.PROFILED_TRAFFIC.values():
+        assert os.path.exists(os.path.join(ROOT, source))
+    assert bench.EVENT_SAMPLES >= 50
