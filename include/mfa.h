@@ -27,8 +27,11 @@
  *     unsupported shapes or types, fp8 without scales, workspace too small) are
  *     rejected before anything is launched.  Conditions only the device can see
  *     have defined results instead: seq_lens[b] <= 0 gives out[b,:,:] = 0;
- *     seq_lens[b] > max_seq_len_hint is treated as max_seq_len_hint; page ids in
- *     the block table are trusted.
+ *     seq_lens[b] > max_seq_len_hint is treated as max_seq_len_hint; a page id
+ *     outside [0, n_pages) that an attention call reads is clamped into that
+ *     range, one that a cache-append call would write to is skipped (the result
+ *     for that sequence is then meaningless, but no memory outside the pools is
+ *     touched).
  *   - Memory of the cache past a sequence's length (padding, the rest of the
  *     last page, unused pages) may hold anything, NaN included; it never
  *     influences the result.
@@ -58,8 +61,15 @@ typedef enum {
     MFA_ERR_INVALID_ARG = 1,             /* NULL/misaligned pointer, size out of range      */
     MFA_ERR_UNSUPPORTED = 2,             /* shape or type this build has no kernel for      */
     MFA_ERR_WORKSPACE_TOO_SMALL = 3,
-    MFA_ERR_HIP = 4                      /* a HIP runtime call or kernel launch failed      */
+    MFA_ERR_HIP = 4,                     /* a HIP runtime call or kernel launch failed      */
+    MFA_ERR_HOST_ALLOC = 5               /* host memory for the context could not be had    */
 } mfa_status;
+
+/* How the cached tokens of a call are shared out among workgroups (mfa_config.schedule). */
+typedef enum {
+    MFA_SCHEDULE_BALANCED = 0,           /* tiles of all sequences end to end, equal ranges */
+    MFA_SCHEDULE_FIXED = 1               /* every sequence cut into the same number of equal chunks of the hint */
+} mfa_schedule;
 
 typedef enum {
     MFA_KV_BF16 = 0,
@@ -80,7 +90,14 @@ typedef struct {
     int32_t max_batch;      /* largest B of any later call (attention and query path)      */
     int32_t max_seq_len;    /* largest max_seq_len_hint of any later call                  */
     int32_t device;         /* HIP device ordinal                                          */
+    int32_t target_workgroups; /* workgroups an attention call aims for; 0 = the default, one per
+                                  compute unit of MI355X (256); 1..4096                           */
+    int32_t schedule;       /* mfa_schedule; MFA_SCHEDULE_BALANCED (0) is the default; batches
+                               above 4096 sequences always take MFA_SCHEDULE_FIXED                 */
 } mfa_config;
+/* Test override: when target_workgroups is 0 / schedule is MFA_SCHEDULE_BALANCED, the environment
+ * variables MFA_TARGET_ITEMS=<n> / MFA_SCHEDULE=fixed, read when a context is created, select the
+ * same things. */
 
 /* Bytes of device workspace a context for `cfg` needs.  Pure host function;
  * returns 0 if cfg is NULL or invalid. */
@@ -191,7 +208,7 @@ MFA_API mfa_status mfa_out_proj(mfa_ctx* ctx, const float* attn_out, const void*
  * Work distribution: for B <= 4096 the 64-token tiles of all sequences, laid end
  * to end, are cut into equal ranges over at most 256 workgroups, whatever the
  * individual lengths are (they are read on the device); larger batches, or a
- * context created with MFA_SCHEDULE=fixed in the environment, cut every sequence
+ * context created with schedule = MFA_SCHEDULE_FIXED, cut every sequence
  * into the same number of equal chunks of max_seq_len_hint instead.  Pieces of a
  * sequence are merged in order of position by the library.
  */
@@ -244,7 +261,7 @@ MFA_API mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_
  *   out  fp32 [B, q_len, n_q_heads, head_dim]     (written)
  * 1 <= q_len <= 4 (larger: MFA_ERR_UNSUPPORTED); q_len = 1 is mfa_decode_attn[_paged].  Two query
  * tokens share one pass over the cache; three and four are worked off as two such pairs, i.e. two
- * passes.  Several query tokens need the balanced work distribution (B <= 4096, no MFA_SCHEDULE=fixed).
+ * passes.  Several query tokens need the balanced work distribution (B <= 4096, schedule MFA_SCHEDULE_BALANCED).
  * Everything else as for q_len = 1.
  */
 MFA_API mfa_status mfa_decode_attn_multi(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,

@@ -18,6 +18,10 @@ MFA_ERR_INVALID_ARG = 1
 MFA_ERR_UNSUPPORTED = 2
 MFA_ERR_WORKSPACE_TOO_SMALL = 3
 MFA_ERR_HIP = 4
+MFA_ERR_HOST_ALLOC = 5
+
+MFA_SCHEDULE_BALANCED = 0
+MFA_SCHEDULE_FIXED = 1
 
 MFA_KV_BF16 = 0
 MFA_KV_FP8_E4M3 = 1
@@ -37,7 +41,7 @@ class MfaConfigC(ctypes.Structure):
         ("n_q_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("d_model", ctypes.c_int32),
         ("q_rank", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("rms_eps", ctypes.c_float),
         ("page_size", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("max_seq_len", ctypes.c_int32),
-        ("device", ctypes.c_int32),
+        ("device", ctypes.c_int32), ("target_workgroups", ctypes.c_int32), ("schedule", ctypes.c_int32),
     ]
 
 
@@ -53,10 +57,13 @@ class MfaConfig:
     max_batch: int = 128
     max_seq_len: int = 32768
     device: int = 0
+    target_workgroups: int = 0          # 0: the library's default (one per compute unit)
+    schedule: int = MFA_SCHEDULE_BALANCED
 
     def to_c(self):
         return MfaConfigC(self.n_q_heads, self.head_dim, self.d_model, self.q_rank, self.softmax_scale,
-                          self.rms_eps, self.page_size, self.max_batch, self.max_seq_len, self.device)
+                          self.rms_eps, self.page_size, self.max_batch, self.max_seq_len, self.device,
+                          self.target_workgroups, self.schedule)
 
 
 _lib = None
@@ -67,13 +74,18 @@ def lib_path():
 
 
 def lib():
-    """Load libmfa.so (building it first only if no built library exists)."""
+    """Load libmfa.so (building it first only if no built library exists; a library older than its sources
+    is loaded as it is, with a warning: rebuild with `python -m paper_2507_19427_amd.build`)."""
     global _lib
     if _lib is not None:
         return _lib
     path = lib_path()
     if not os.path.exists(path):
         _build.build(force=True)
+    elif path == _build.LIB and _build._stale():
+        import warnings
+        warnings.warn(f"{path} is older than the sources under csrc/: the tests and benchmarks run the OLD binary "
+                      "until it is rebuilt (python -m paper_2507_19427_amd.build)", RuntimeWarning, stacklevel=2)
     L = ctypes.CDLL(path)
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
     cfgp = ctypes.POINTER(MfaConfigC)
@@ -472,7 +484,8 @@ def mfa_out_proj(ctx: MfaContext, attn_out, w_o, y=None):
 class PreparedDecodeAttn:
     """mfa_decode_attn (q [B,H,D]) or mfa_decode_attn_multi (q [B,q_len,H,D]) with its arguments marshalled
     once: calling the object only crosses the C boundary (for loops that must not pay Python-side checks
-    per step).  The tensors are kept alive."""
+    per step).  The tensors are kept alive.  The work is enqueued on the stream that is current when the
+    object is called (not the one that was current when it was made)."""
 
     def __init__(self, ctx: MfaContext, q, k_cache, v_cache, seq_lens, max_seq_len_hint, out, k_scale=None,
                  v_scale=None):
@@ -485,9 +498,9 @@ class PreparedDecodeAttn:
         self._fn = getattr(lib(), self._name)
         head = (ctx.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
                 _kv_dtype(k_cache), k_cache.shape[1], _ptr(seq_lens), int(max_seq_len_hint), q.shape[0])
-        self._args = head + ((q.shape[1],) if multi else ()) + (_ptr(out), _stream())
+        self._args = head + ((q.shape[1],) if multi else ()) + (_ptr(out),)
 
     def __call__(self):
-        st = self._fn(*self._args)
+        st = self._fn(*self._args, _stream())
         if st != MFA_OK:
             raise MfaError(st, self._name)

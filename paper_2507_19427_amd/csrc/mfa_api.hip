@@ -13,7 +13,7 @@ using namespace mfa;
 struct mfa_ctx {
     mfa_config cfg;
     int32_t target_items;      // workgroups the planner aims for (one per compute unit by default)
-    bool fixed_splits;         // MFA_SCHEDULE=fixed: every sequence cut into the same number of equal chunks
+    bool fixed_splits;         // MFA_SCHEDULE_FIXED: every sequence cut into the same number of equal chunks
     size_t max_items;          // bound on B * n_splits over all admissible calls
     float* ws_acc;
     float* ws_ml;
@@ -67,14 +67,24 @@ hipError_t static_scratch_for_device(int device, unsigned char** out)
     return hipSuccess;
 }
 
-int32_t target_items_from_env()
+// Workgroups an attention call aims for: the configuration's figure, else (test override) the
+// environment's, else one per compute unit.
+int32_t target_items_of(const mfa_config* c)
 {
+    if (c->target_workgroups >= 1 && c->target_workgroups <= 4096) return c->target_workgroups;
     const char* s = std::getenv("MFA_TARGET_ITEMS");
     if (s) {
         const long v = std::strtol(s, nullptr, 10);
         if (v >= 1 && v <= 4096) return (int32_t)v;
     }
     return kDefaultTargetItems;
+}
+
+bool fixed_schedule_of(const mfa_config* c)
+{
+    if (c->schedule == MFA_SCHEDULE_FIXED) return true;
+    const char* sch = std::getenv("MFA_SCHEDULE");
+    return sch && std::string(sch) == "fixed";
 }
 
 bool config_ok(const mfa_config* c)
@@ -87,6 +97,8 @@ bool config_ok(const mfa_config* c)
     if (!(c->softmax_scale > 0.f) || !std::isfinite(c->softmax_scale)) return false;
     if (!(c->rms_eps >= 0.f) || !std::isfinite(c->rms_eps)) return false;
     if (c->device < 0) return false;
+    if (c->target_workgroups < 0 || c->target_workgroups > 4096) return false;
+    if (c->schedule != MFA_SCHEDULE_BALANCED && c->schedule != MFA_SCHEDULE_FIXED) return false;
     return true;
 }
 
@@ -189,7 +201,7 @@ extern "C" {
 size_t mfa_decode_workspace_bytes(const mfa_config* cfg)
 {
     if (!config_ok(cfg) || !config_supported(cfg)) return 0;
-    return carve(cfg, target_items_from_env()).total;
+    return carve(cfg, target_items_of(cfg)).total;
 }
 
 mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t workspace_bytes, mfa_ctx** out_ctx)
@@ -198,7 +210,7 @@ mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t work
     if (!out_ctx || !config_ok(cfg) || !d_workspace) return MFA_ERR_INVALID_ARG;
     if (!config_supported(cfg)) return MFA_ERR_UNSUPPORTED;
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return MFA_ERR_INVALID_ARG;
-    const int32_t target = target_items_from_env();
+    const int32_t target = target_items_of(cfg);
     const Carve w = carve(cfg, target);
     if (workspace_bytes < w.total) return MFA_ERR_WORKSPACE_TOO_SMALL;
 
@@ -216,13 +228,10 @@ mfa_status mfa_decode_init(const mfa_config* cfg, void* d_workspace, size_t work
     if (e != hipSuccess) return MFA_ERR_HIP;
 
     mfa_ctx* ctx = new (std::nothrow) mfa_ctx;
-    if (!ctx) return MFA_ERR_INVALID_ARG;
+    if (!ctx) return MFA_ERR_HOST_ALLOC;
     ctx->cfg = *cfg;
     ctx->target_items = target;
-    {
-        const char* sch = std::getenv("MFA_SCHEDULE");
-        ctx->fixed_splits = sch && std::string(sch) == "fixed";
-    }
+    ctx->fixed_splits = fixed_schedule_of(cfg);
     ctx->max_items = w.max_items;
     unsigned char* base = static_cast<unsigned char*>(d_workspace);
     ctx->ws_acc = reinterpret_cast<float*>(base + w.acc);
@@ -249,6 +258,7 @@ const char* mfa_status_string(mfa_status s)
         case MFA_ERR_UNSUPPORTED: return "unsupported shape or type";
         case MFA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case MFA_ERR_HIP: return "HIP runtime error";
+        case MFA_ERR_HOST_ALLOC: return "out of host memory";
     }
     return "unknown status";
 }

@@ -33,7 +33,8 @@ def test_library_exports_every_declared_symbol():
 def test_status_strings():
     L = B.lib()
     assert L.mfa_status_string(0) == b"ok"
-    assert len({L.mfa_status_string(i) for i in range(5)}) == 5
+    assert len({L.mfa_status_string(i) for i in range(6)}) == 6
+    assert L.mfa_status_string(B.MFA_ERR_HOST_ALLOC) == b"out of host memory"
 
 
 def test_workspace_bytes_is_a_pure_host_function():
@@ -57,6 +58,9 @@ def test_workspace_bytes_is_a_pure_host_function():
     (dict(max_seq_len=0), B.MFA_ERR_INVALID_ARG),
     (dict(softmax_scale=float("nan")), B.MFA_ERR_INVALID_ARG),
     (dict(d_model=100), B.MFA_ERR_INVALID_ARG),
+    (dict(target_workgroups=-1), B.MFA_ERR_INVALID_ARG),
+    (dict(target_workgroups=5000), B.MFA_ERR_INVALID_ARG),
+    (dict(schedule=7), B.MFA_ERR_INVALID_ARG),
 ])
 def test_init_rejects_bad_configs_before_any_device_call(kw, status):
     L = B.lib()
@@ -65,6 +69,17 @@ def test_init_rejects_bad_configs_before_any_device_call(kw, status):
     fake_ws = ctypes.c_void_p(4096)          # never dereferenced: the config is checked first
     assert L.mfa_decode_init(ctypes.byref(c), fake_ws, 1 << 40, ctypes.byref(handle)) == status
     assert handle.value is None
+
+
+def test_schedule_knobs_are_configuration_fields_with_an_environment_override(monkeypatch):
+    """The workspace size follows the number of workgroups aimed for: the field decides, the environment
+    variable only when the field is left at its default."""
+    base = B.mfa_decode_workspace_bytes(B.MfaConfig(max_batch=8, max_seq_len=4096))
+    more = B.mfa_decode_workspace_bytes(B.MfaConfig(max_batch=8, max_seq_len=4096, target_workgroups=1024))
+    assert more > base
+    monkeypatch.setenv("MFA_TARGET_ITEMS", "1024")
+    assert B.mfa_decode_workspace_bytes(B.MfaConfig(max_batch=8, max_seq_len=4096)) == more
+    assert B.mfa_decode_workspace_bytes(B.MfaConfig(max_batch=8, max_seq_len=4096, target_workgroups=256)) == base
 
 
 def test_init_rejects_null_misaligned_and_small_workspace():

@@ -1,19 +1,13 @@
-"""Host-side check of the compiled attention kernels for the 8-bit and 4-bit caches.
-
-Its register pipeline loads cache data with inline-assembly loads and waits for them with an
-inline-assembly s_waitcnt; between the two the compiler does not know that the destination registers are
-still in flight.  The code is written so that it has no reason to touch them (one loading statement and one
-waiting statement per register set inside the loop), but nothing in the language forbids the register
-allocator from copying such a register to another one before the wait, which would copy a value that has
-not arrived.  This test compiles the kernel to assembly (no GPU needed) and verifies, for every step of the
-pipeline loop, that no register written by one of those loads is read by a move before the next explicit
-wait, and that the loop's explicit waits are the partial ones the pipeline counts on."""
+"""Host-side check of the compiled attention kernels (the checker is paper_2507_19427_amd/asm_check.py, which
+the build itself runs on every library it produces).  Here: the same checks on a fresh compilation of
+mfa_attn.hip, kernel by kernel, and the checker against planted mistakes."""
 import os
-import re
 import shutil
 import subprocess
 
 import pytest
+
+from paper_2507_19427_amd import asm_check as A
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "paper_2507_19427_amd", "csrc", "mfa_attn.hip")
@@ -32,72 +26,19 @@ def asm_text(tmp_path_factory):
     return out.read_text()
 
 
-def _kernel_body(text, mangled):
-    start = text.index("\n" + mangled + ":")
-    end = text.index(".size\t" + mangled, start)
-    return text[start:end].split("\n")
+@pytest.mark.parametrize("paged,q_len,bits", A.PIPELINE_KERNELS)
+def test_lowbit_pipeline_registers_stay_untouched_between_load_and_wait(asm_text, paged, q_len, bits):
+    A.check_pipeline(A.kernel_body(asm_text, A.lowbit_kernel_name(paged, q_len, bits)), A.OPS_PER_STEP[bits])
 
 
-def _regs(token):
-    m = re.fullmatch(r"v\[(\d+):(\d+)\]", token)
-    if m:
-        return set(range(int(m.group(1)), int(m.group(2)) + 1))
-    m = re.fullmatch(r"v(\d+)", token)
-    return {int(m.group(1))} if m else set()
+def test_no_attention_kernel_uses_scratch_memory(asm_text):
+    scratch = {k: v for k, v in A.scratch_bytes(asm_text).items() if "decode_" in k}
+    assert len(scratch) == 12                              # bf16 / 8 bit / 4 bit x paged or not x one or two query tokens
+    assert all(v == 0 for v in scratch.values()), scratch
 
 
-def _check_pipeline(lines, ops_per_step=5):
-    in_asm = False
-    queue = []                 # vector-memory operations in issue order: the registers each one writes
-                               # (empty for direct-to-LDS loads, stores and compiler-made loads)
-    partial_waits = 0
-
-    def in_flight():
-        regs = set()
-        for r in queue:
-            regs |= r
-        return regs
-
-    for ln in lines:
-        t = ln.strip()
-        if t.startswith(";;#ASMSTART"):
-            in_asm = True
-            continue
-        if t.startswith(";;#ASMEND"):
-            in_asm = False
-            continue
-        if not t or t.startswith(";") or t.startswith("."):
-            continue
-        op, _, rest = t.partition(" ")
-        operands = [o.strip() for o in rest.split(",")] if rest else []
-        if op.startswith("global_load") or op.startswith("global_store") or op.startswith("buffer_"):
-            tracked = in_asm and op in ("global_load_dwordx4", "global_load_dword")
-            queue.append(_regs(operands[0]) if tracked else set())
-            continue
-        if op == "s_waitcnt" and "vmcnt" in rest:
-            left = int(re.search(r"vmcnt\((\d+)\)", rest).group(1))
-            if in_asm and left == ops_per_step:
-                partial_waits += 1
-            if not in_asm and partial_waits > 0:
-                # a compiler-made vector-memory wait inside the pipeline loop: it must not reach the
-                # pipeline's own loads (the compiler does not count them, so its number is too small)
-                assert not in_flight(), f"compiler-inserted wait drains the pipeline: {t}"
-            queue = queue[max(0, len(queue) - left):] if left else []
-            continue
-        if op.startswith("v_mov") or op.startswith("v_pk_mov") or op.startswith("v_accvgpr"):
-            sources = set()
-            for o in operands[1:]:
-                sources |= _regs(o)
-            assert not (sources & in_flight()), f"in-flight register copied before its wait: {t}"
-    assert partial_waits >= 2, "the two steps of the unrolled loop each wait for all but the youngest step's loads"
-
-
-@pytest.mark.parametrize("bits,ops_per_step", [(8, 5), (4, 3)])
-@pytest.mark.parametrize("q_len", [1, 2])
-@pytest.mark.parametrize("paged", [0, 1])
-def test_lowbit_pipeline_registers_stay_untouched_between_load_and_wait(asm_text, paged, q_len, bits, ops_per_step):
-    name = f"_ZN3mfa20decode_lowbit_kernelILb{paged}ELi{q_len}ELi{bits}EEEvNS_8AttnArgsE"
-    _check_pipeline(_kernel_body(asm_text, name), ops_per_step)
+def test_everything_the_build_checks(asm_text):
+    A.check_attention_asm(asm_text)
 
 
 def _snippet(between):
@@ -107,9 +48,23 @@ def _snippet(between):
     return wait + load + filler + wait + load + filler + between + wait + ["v_mov_b32_e32 v20, v11"]
 
 
-def test_the_checker_itself_catches_a_copy_and_a_drain():
-    _check_pipeline(_snippet([]))                                   # clean: the copy comes after the wait
-    with pytest.raises(AssertionError, match="copied before its wait"):
-        _check_pipeline(_snippet(["v_mov_b32_e32 v20, v11"]))
+def test_the_checker_itself_catches_planted_mistakes():
+    A.check_pipeline(_snippet([]))                                   # clean: the copy comes after the wait
+    A.check_pipeline(_snippet(["v_add_f32_e32 v21, v14, v15"]))      # clean: other registers
+    for bad in ("v_mov_b32_e32 v20, v11",                            # copied
+                "v_add_f32_e32 v21, v10, v15",                       # read by arithmetic
+                "v_mov_b32_e32 v12, v30",                            # overwritten
+                "v_pk_mul_f32 v[40:41], v[12:13], v[2:3]",           # read as part of a register range
+                "ds_write_b128 v7, v[10:13]"):                       # stored to LDS
+        with pytest.raises(AssertionError, match="touched before its wait"):
+            A.check_pipeline(_snippet([bad]))
+    with pytest.raises(AssertionError, match="touched by a memory instruction"):
+        A.check_pipeline(_snippet(["scratch_store_dwordx4 off, v[10:13], off offset:16"]))   # spilled
     with pytest.raises(AssertionError, match="drains the pipeline"):
-        _check_pipeline(_snippet(["s_waitcnt vmcnt(0)"]))
+        A.check_pipeline(_snippet(["s_waitcnt vmcnt(0)"]))
+
+
+def test_scratch_directive_parser():
+    text = "\n".join(["\t.amdhsa_kernel _ZN3mfa18decode_x", "\t\t.amdhsa_private_segment_fixed_size 24", "\t.end_amdhsa_kernel",
+                      "\t.amdhsa_kernel other", "\t\t.amdhsa_private_segment_fixed_size 0", "\t.end_amdhsa_kernel"])
+    assert A.scratch_bytes(text) == {"_ZN3mfa18decode_x": 24, "other": 0}

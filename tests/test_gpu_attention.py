@@ -69,11 +69,10 @@ def test_hint_larger_than_lengths_and_clamping():
     assert U.row_normalised_error(got2, U.run_oracle(trunc)) <= U.TOL_BF16
 
 
-def test_single_split_path(monkeypatch):
+def test_single_split_path():
     """With one work item per sequence the kernel writes the final result itself (no merge pass)."""
     _announce("single split")
-    monkeypatch.setenv("MFA_TARGET_ITEMS", "1")
-    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=8, max_seq_len=2048))
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=8, max_seq_len=2048, target_workgroups=1))
     assert mfa.mfa_decode_num_splits(ctx, 4, 1000) == 1
     case = W.make_contiguous_case("one", 141, B=4, S=1000, seq_lens=[1000, 1, 640, 0], poison=True)
     got = U.run_gpu(ctx, case)

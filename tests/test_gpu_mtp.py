@@ -153,15 +153,14 @@ def test_four_tokens_paged_bitwise_equal_to_contiguous():
     assert np.array_equal(got_p, _run_gpu(ctx, contig, qm, hint=400))
 
 
-def test_unsupported_query_counts_are_refused(monkeypatch):
+def test_unsupported_query_counts_are_refused():
     _announce("q_len=5 and q_len=2 on fixed splits are refused")
     case = W.make_contiguous_case("mtpbad", 761, B=2, S=64, seq_lens=[64, 10], poison=True)
     q3 = W.make_multi_query(case, 5, 762)
     with pytest.raises(mfa.MfaError) as ei:
         _run_gpu(U.get_ctx(), case, q3)
     assert ei.value.status == mfa.MFA_ERR_UNSUPPORTED
-    monkeypatch.setenv("MFA_SCHEDULE", "fixed")
-    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=16, max_seq_len=8192))
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=16, max_seq_len=8192, schedule=mfa.MFA_SCHEDULE_FIXED))
     with pytest.raises(mfa.MfaError) as ei:
         _run_gpu(ctx, case, W.make_multi_query(case, 2, 763))
     assert ei.value.status == mfa.MFA_ERR_UNSUPPORTED

@@ -63,7 +63,7 @@ def _one_case(rng, i, ctx):
     return err / tol
 
 
-@pytest.mark.parametrize("seed", [11, 12])
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
 def test_random_sweep(seed):
     print(f"\n[case] random sweep, seed {seed}", flush=True)
     rng = np.random.default_rng(seed)

@@ -134,15 +134,20 @@ def test_two_query_tokens_with_a_thousand_sequences():
 
 
 def test_fixed_split_schedule_agrees(monkeypatch):
-    """MFA_SCHEDULE=fixed selects the schedule with equal chunks per sequence; both must match the oracle."""
+    """schedule = MFA_SCHEDULE_FIXED selects the schedule with equal chunks per sequence; both must match the
+    oracle.  The environment override (MFA_SCHEDULE=fixed at context creation) selects the same code path."""
     _announce("fixed-split schedule")
     lens = [0, 3000, 1, 64, 5000, 129, 2048]
     case = W.make_contiguous_case("fixed", 351, B=len(lens), S=5008, seq_lens=lens, poison=True)
-    monkeypatch.setenv("MFA_SCHEDULE", "fixed")
-    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=16, max_seq_len=8192))
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=16, max_seq_len=8192, schedule=mfa.MFA_SCHEDULE_FIXED))
     got_fixed = _check(case, ctx, U.TOL_BF16)
     ctx.close()
+    monkeypatch.setenv("MFA_SCHEDULE", "fixed")
+    ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=16, max_seq_len=8192))
+    got_env = _check(case, ctx, U.TOL_BF16)
+    ctx.close()
     monkeypatch.delenv("MFA_SCHEDULE")
+    assert np.array_equal(got_fixed, got_env)
     got_bal = _check(case, U.get_ctx(), U.TOL_BF16)
     assert U.row_normalised_error(got_fixed, got_bal.astype(np.float64)) <= U.TOL_BF16
 
