@@ -166,32 +166,34 @@ def build_workload(key, mfa, W, n_sets):
         if q_len == 1:
             w.case = case
         w.extra_config = {"query_tokens_per_sequence": q_len}
-    elif key in ("cfg2q2", "fp8q2"):
-        # Two new tokens per sequence in one pass over the cache (the multi-token step of Section 5.2):
-        # same cache shapes as configs[1] / the cache of configs[4], twice the arithmetic per byte.
+    elif key in ("cfg2q2", "cfg2q3", "cfg2q4", "fp8q2"):
+        # Several new tokens per sequence in one pass over the cache (the multi-token step of Section 5.2):
+        # same cache shapes as configs[1] / the cache of configs[4], q_len times the arithmetic per byte.
         fp8 = key == "fp8q2"
+        q_len = int(key[-1])
         case = (W.make_contiguous_case(key, 6, B=128, S=8192, kv_dtype="fp8", poison=False) if fp8
                 else W.config2_step3(poison=False))
         B, S = case.B, case.k.shape[1]
         w.ctx = mfa.mfa_decode_init(mfa.MfaConfig(max_batch=B, max_seq_len=S))
-        q, lens = W.make_multi_query(case, 2, 9).cuda(), case.seq_lens.cuda()
+        q, lens = W.make_multi_query(case, q_len, 9).cuda(), case.seq_lens.cuda()
         ks, vs = _roll_sets(case.k.cuda(), n_sets), _roll_sets(case.v.cuda(), n_sets)
         kss = _roll_sets(case.k_scale.cuda(), n_sets) if fp8 else [None] * n_sets
         vss = _roll_sets(case.v_scale.cuda(), n_sets) if fp8 else [None] * n_sets
-        out = torch.empty(B, 2, 64, 256, dtype=torch.float32, device="cuda")
+        out = torch.empty(B, q_len, 64, 256, dtype=torch.float32, device="cuda")
         w.steps = [mfa.PreparedDecodeAttn(w.ctx, q, ks[j], vs[j], lens, S, out, k_scale=kss[j], v_scale=vss[j])
                    for j in range(n_sets)]
         w.read_pairs = list(zip(ks, vs))
-        w.desc = ("two query tokens per sequence: B=%d, 64 q heads, 1 shared K/V head, head_dim 256, ctx %d, "
-                  "contiguous %s KV" % (B, S, "fp8 e4m3 (per-token fp32 scales)" if fp8 else "bf16"))
-        w.metric = "KV tokens/s, MFA decode attention with 2 query tokens, B=%d, ctx %d, %s, 1 GPU" % (
-            B, S, "fp8 KV" if fp8 else "bf16")
+        w.desc = ("%d query tokens per sequence: B=%d, 64 q heads, 1 shared K/V head, head_dim 256, ctx %d, "
+                  "contiguous %s KV" % (q_len, B, S, "fp8 e4m3 (per-token fp32 scales)" if fp8 else "bf16"))
+        w.metric = "KV tokens/s, MFA decode attention with %d query tokens, B=%d, ctx %d, %s, 1 GPU" % (
+            q_len, B, S, "fp8 KV" if fp8 else "bf16")
         w.dtype = "bf16 (fp8 e4m3 KV storage)" if fp8 else "bf16"
-        w.kernel = "mfa::decode_lowbit_kernel<false, 2, 8>" if fp8 else "mfa::decode_bf16_kernel<false, 2>"
+        w.kernel = ("mfa::decode_lowbit_kernel<false, 2, 8>" if fp8 else
+                    "mfa::decode_bf16_kernel<false, 2>" if q_len == 2 else "mfa::decode_bf16_multi_kernel<false, %d>" % q_len)
         w.kv_bytes_per_token = 520 if fp8 else 1024
-        w.T, w.B, w.q_len = case.kv_tokens, B, 2
+        w.T, w.B, w.q_len = case.kv_tokens, B, q_len
         w.attn_calls, w.attn_only = w.steps, True
-        w.extra_config = {"query_tokens_per_sequence": 2}
+        w.extra_config = {"query_tokens_per_sequence": q_len}
     elif key in ("layer8k", "layer32k", "layer8k_fp8", "layer32k_fp8"):
         # One whole attention layer of a decode step, the unit of the paper's attention-latency table
         # (Section 7.3: 64 sequences per GPU, context 8K / 32K): query path, key/value projection of the
@@ -257,7 +259,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "cfg2q2", "fp8q2", "fp4", "fp4q2", "layer8k", "layer32k", "layer8k_fp8", "layer32k_fp8"), default="cfg2")
+    ap.add_argument("--workload", choices=("cfg2", "cfg3", "cfg4", "cfg5", "cfg2q2", "cfg2q3", "cfg2q4", "fp8q2", "fp4", "fp4q2", "layer8k", "layer32k", "layer8k_fp8", "layer32k_fp8"), default="cfg2")
     ap.add_argument("--buffer-sets", type=int, default=None, help="distinct KV buffer sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")

@@ -260,8 +260,10 @@ MFA_API mfa_status mfa_debug_gather_paged(mfa_ctx* ctx, const void* pool, int32_
  *   q    bf16 [B, q_len, n_q_heads, head_dim]
  *   out  fp32 [B, q_len, n_q_heads, head_dim]     (written)
  * 1 <= q_len <= 4 (larger: MFA_ERR_UNSUPPORTED); q_len = 1 is mfa_decode_attn[_paged].  Two query
- * tokens share one pass over the cache; three and four are worked off as two such pairs, i.e. two
- * passes.  Several query tokens need the balanced work distribution (B <= 4096, schedule MFA_SCHEDULE_BALANCED).
+ * tokens share one pass over the cache; three and four share one pass over a bf16 cache when
+ * B <= 512, and are otherwise (8-bit and 4-bit caches, larger batches) worked off as two pairs, i.e.
+ * two passes.  Several query tokens need the balanced work distribution (B <= 4096, schedule
+ * MFA_SCHEDULE_BALANCED).
  * Everything else as for q_len = 1.
  */
 MFA_API mfa_status mfa_decode_attn_multi(mfa_ctx* ctx, const void* q, const void* k_cache, const void* v_cache,

@@ -136,9 +136,9 @@ Carve carve(const mfa_config* c, int32_t target)
     w.qproj = plan_qproj(c->d_model, c->q_rank);
     w.rows_pad = (c->max_batch + kQProjRows - 1) / kQProjRows * kQProjRows;
     size_t off = 0;
-    // partial results: one slot per (workgroup segment, query token), up to two query tokens
-    w.acc = off; off = align_up(off + 2 * w.max_items * kPartialAccFloats * sizeof(float), 256);
-    w.ml = off;  off = align_up(off + 2 * w.max_items * kPartialMlFloats * sizeof(float), 256);
+    // partial results: one slot per (workgroup segment, query token of a launch), up to kMaxQueryTokens of them
+    w.acc = off; off = align_up(off + kMaxQueryTokens * w.max_items * kPartialAccFloats * sizeof(float), 256);
+    w.ml = off;  off = align_up(off + kMaxQueryTokens * w.max_items * kPartialMlFloats * sizeof(float), 256);
     w.seg = off; off = align_up(off + (size_t)c->max_batch * 2 * sizeof(int32_t), 256);
     // split-K partials of whichever product is running, and the bf16 k-step-major activations of the
     // second query product / the output projection
@@ -186,6 +186,7 @@ void fill_common(const mfa_ctx* ctx, AttnArgs& a, int32_t B, int32_t hint)
     a.B = B;
     a.q_len = 1;
     a.q0 = 0;
+    a.n_here = 1;
     a.max_seq_len_hint = hint;
     a.ws_acc = ctx->ws_acc;
     a.ws_ml = ctx->ws_ml;

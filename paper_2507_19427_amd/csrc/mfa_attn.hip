@@ -149,6 +149,140 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     }
 }
 
+// ---- Three or four query tokens per sequence in ONE pass over a bf16 cache (Section 5.2: the new tokens of a
+// multi-token step share the cache read, which multiplies the arithmetic per byte by their number).
+// A workgroup is four waves, one per SIMD, wave = head group: a wave holds all NT query tokens of its 16 heads
+// (NT x 32 registers of query fragments, NT x 64 accumulator registers: only one wave fits a SIMD's register
+// file) and works through both units of every tile; key and value fragments read from LDS are shared by the NT
+// tokens (process_unit_multi).  Same tiles, same two-slot ring and same schedule as decode_bf16_kernel; each wave
+// brings 16 rows of a tile.  Query token j attends to the first len - (q_len - 1 - j) cached tokens.  Batches of
+// at most 512 sequences (every wave works the schedule out by itself).
+constexpr int kMultiThreads = 256;
+template <bool PAGED, int NT>
+__global__ __launch_bounds__(kMultiThreads) void decode_bf16_multi_kernel(AttnArgs a)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const lds_ptr_t lds_base = (lds_ptr_t)smem;
+    const uint32_t lds_addr0 = (uint32_t)(uintptr_t)lds_base;
+
+    const int lane = threadIdx.x & 63;
+    const int wq = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15;
+    const int g = lane >> 4;
+
+    auto issue_tile = [&](const Segment& sg, int tile, int slot, int page) {
+        const int tile_t0 = sg.t0 + tile * kTile;
+        const int64_t row0 = tile_row0<PAGED>(a, sg.b, tile_t0, page);
+        const unsigned char* k_tile = (const unsigned char*)a.k + row0 * 512;
+        const unsigned char* v_tile = (const unsigned char*)a.v + row0 * 512;
+        int lane_now = lane;                                          // (the lane's offsets are formed here, per tile, not
+        asm volatile("" : "+v"(lane_now));                            // ahead of the tile loop and kept in scarce registers)
+        const int p16 = lane_now & 31;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int row = 16 * wq + 2 * u + (lane_now >> 5);        // row of the tile this lane fills
+            int in_tile = row;
+            if (tile_t0 + row > sg.t1 - 1) in_tile = sg.t1 - 1 - tile_t0;
+            const int key = row & 15;
+            const int ck = p16 ^ key;
+            const int cv = ((((p16 >> 1) ^ key) << 1) | (p16 & 1));
+            const int first_row = 16 * wq + 2 * u;                     // wave-uniform
+            const uint32_t dst = lds_addr0 + slot * kSlotBytes + (first_row >> 5) * kUnitBytes + (first_row & 31) * 512;
+            load_to_lds_16B(k_tile, (uint32_t)(in_tile * 512 + ck * 16), dst);
+            load_to_lds_16B(v_tile, (uint32_t)(in_tile * 512 + cv * 16), dst + kUnitVOffset);
+        }
+    };
+    QFrags<16> q[NT];
+    auto load_q = [&](const Segment& sg) {
+        int lane_now = lane;                                          // (addresses formed here, once per segment)
+        asm volatile("" : "+v"(lane_now));
+#pragma unroll
+        for (int t = 0; t < NT; ++t) load_q_fragments(q[t].f, a.q, a.q_len * sg.b + a.q0 + t, 16 * wq + (lane_now & 15), lane_now >> 4);
+    };
+
+    // A word of LDS behind the schedule's tables: set by a wave whose unit was refused (a score more than
+    // 2^kFixedReferenceLag above its head's reference exponent), seen by all waves after the next barrier.
+    constexpr int kRestartFlag = kAttnLdsTotal - 4;
+    Schedule sched = schedule_begin(a, lds_base);
+    Segment r;
+    bool first_segment = true;
+    while (schedule_next(a, lds_base, sched, r)) {
+        if (!first_segment) __syncthreads();          // every wave is done with the previous segment's tiles
+        first_segment = false;
+        // Every segment leaves a partial result, also one that covers its whole sequence: partials are stored
+        // straight from the accumulation registers, while a final result would have to pass all of them through
+        // ordinary registers to be normalised.  The merge kernel normalises (AttnArgs::n_here >= 3).
+        r.final_result = false;
+        load_q(r);
+        int t1_mine[NT];
+        float m_floor[NT];                            // reference exponents handed to the next attempt (-inf: none)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int end_mine = r.len - (a.q_len - 1 - a.q0 - t);
+            t1_mine[t] = r.t1 < end_mine ? r.t1 : end_mine;
+            m_floor[t] = -INFINITY;
+        }
+        WaveState st[NT];
+        // One attempt streams the segment with fixed reference exponents.  If a unit is refused, its wave notes the
+        // exponents it needs, raises the flag and stops computing; at the next barrier all waves see the flag and
+        // the segment is streamed again from its first tile (every attempt ends with a higher reference for some
+        // head, and a reference never exceeds the head's largest score: the attempts end).  Plausible attention
+        // scores never get here; correctness does not depend on that.
+        for (bool again = true; again;) {
+            again = false;
+            if (threadIdx.x == 0) *LDS_AT(int, lds_base, kRestartFlag) = 0;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                init_state(st[t]);
+                st[t].m = m_floor[t];
+            }
+            issue_tile(r, 0, 0, lookup_page<PAGED>(a, r.b, r.t0));
+            int page_next = r.n_tiles > 1 ? lookup_page<PAGED>(a, r.b, r.t0 + kTile) : 0;
+            bool refused = false;
+            for (int it = 0; it < r.n_tiles; ++it) {
+                const int slot = it & 1;
+                wait_vmem_all();
+                __syncthreads();                       // tile it has landed; the flag store of attempt start / of a refusal is visible
+                if (*LDS_AT(int, lds_base, kRestartFlag) != 0) { again = true; break; }
+                if (it + 1 < r.n_tiles) {
+                    issue_tile(r, it + 1, slot ^ 1, page_next);
+                    if (it + 2 < r.n_tiles) page_next = lookup_page<PAGED>(a, r.b, r.t0 + (it + 2) * kTile);
+                }
+                if (refused) continue;
+#pragma unroll 1
+                for (int u = 0; u < 2; ++u) {
+                    const int unit = slot * kSlotBytes + u * kUnitBytes;
+                    float m_wanted[NT];
+                    if (!process_unit_multi<NT>(st, q, lds_base, unit, unit + kUnitVOffset, r.t0 + it * kTile + u * kUnitTokens,
+                                                t1_mine, a.scale_log2e, n, g, m_wanted)) {
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) m_floor[t] = fmaxf(m_floor[t], m_wanted[t]);
+                        if (lane == 0) *LDS_AT(int, lds_base, kRestartFlag) = 1;
+                        refused = true;
+                        break;
+                    }
+                }
+            }
+            if (!again) {
+                // the last tile's refusal (if any) has not met a barrier yet
+                __syncthreads();
+                again = *LDS_AT(int, lds_base, kRestartFlag) != 0;
+            }
+            if (again) {
+                wait_vmem_all();                       // a tile may still be on its way into the ring
+                __syncthreads();                       // every wave has read the flag and left the tile loop
+            }
+        }
+        int lane_now = lane;                          // (the result's addresses are formed here, once per segment)
+        asm volatile("" : "+v"(lane_now));
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            finish_segment_two(st[t], a, r, t, wq, lane_now);
+            __builtin_amdgcn_sched_barrier(0);        // one query token's accumulators at a time through ordinary registers
+        }
+    }
+}
+
 // ---- 8-bit and 4-bit caches (BITS = 8: e4m3 codes, 256 B per row; BITS = 4: e2m1 codes two per byte,
 // 128 B per row; one fp32 scale per token and tensor beside either).
 // Keys stay codes all the way: each tile's rows go by direct loads into a ring of three LDS slots and
@@ -392,7 +526,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
 // taken four at a time so that their loads are independent and in flight together.
 __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 {
-    const int n_here = a.q_len == 1 ? 1 : 2;                          // query tokens of this launch
+    const int n_here = a.n_here;                                      // query tokens of this launch
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B * n_here * 4096 float4
     const int p = (int)(idx & 4095);                                  // position in the partial's lane-order layout
     const int bq = (int)(idx >> 12);                                  // sequence * n_here + query token of the launch
@@ -414,7 +548,8 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
         if (L == 0) { *o = make_float4(0.f, 0.f, 0.f, 0.f); return; }
         item0 = (size_t)a.ws_seg[2 * b];
         n_valid = a.ws_seg[2 * b + 1];
-        if (n_valid == 1) return;                                     // one workgroup held it all and wrote the result
+        if (n_valid == 1 && n_here < 3) return;                       // one workgroup held it all and wrote the result
+                                                                      // (the one-pass kernel for 3 / 4 tokens never does)
     } else {
         if (L == 0) return;                                           // zeros were written by the first split
         n_valid = (L + a.chunk_tokens - 1) / a.chunk_tokens;          // <= n_splits
@@ -539,8 +674,21 @@ const void* attn_kernel(mfa_kv_dtype kv_dtype, bool paged)
 
 }  // namespace
 
+namespace {
+const void* multi_kernel(int q_len, bool paged)
+{
+    if (q_len == 3) return paged ? (const void*)decode_bf16_multi_kernel<true, 3> : (const void*)decode_bf16_multi_kernel<false, 3>;
+    return paged ? (const void*)decode_bf16_multi_kernel<true, 4> : (const void*)decode_bf16_multi_kernel<false, 4>;
+}
+}  // namespace
+
 hipError_t prepare_decode_attn_kernels()
 {
+    for (int q_len = 3; q_len <= 4; ++q_len)
+        for (int paged = 0; paged < 2; ++paged) {
+            const hipError_t e = hipFuncSetAttribute(multi_kernel(q_len, paged != 0), hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsTotal);
+            if (e != hipSuccess) return e;
+        }
     for (int dt = 0; dt < 3; ++dt)
         for (int paged = 0; paged < 2; ++paged) {
             const mfa_kv_dtype kvd = dt == 0 ? MFA_KV_BF16 : (dt == 1 ? MFA_KV_FP8_E4M3 : MFA_KV_FP4_E2M1);
@@ -565,14 +713,31 @@ hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStrea
     // (With more than two query tokens: the first pair's.)
     if (!(ev_before && ev_after)) ev_before = ev_after = nullptr;
     const unsigned lds_bytes = a.n_wgs > 0 ? kAttnLdsTotal : kSchedLdsOffset;   // the schedule's arrays only if used
+    const unsigned merge_blocks_per_token = (unsigned)(((size_t)a.B * kHeads * (kHeadDim / 4) + 255) / 256);
+    // Three and four query tokens over a bf16 cache, batches the per-wave schedule covers: one pass over the cache
+    // by the kernel that keeps all of a sequence's query tokens in one wave.
+    if (a.q_len >= 3 && kv_dtype == MFA_KV_BF16 && a.B <= kWaveScanChunks * 64) {
+        AttnArgs args = a;
+        args.q0 = 0;
+        args.n_here = a.q_len;
+        void* params[] = {&args};
+        hipError_t e = hipExtLaunchKernel(multi_kernel(a.q_len, a.block_table != nullptr), grid, dim3(kMultiThreads), params,
+                                          kAttnLdsTotal, stream, ev_before, ev_after, 0);
+        if (e != hipSuccess) return e;
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(merge_splits_kernel, dim3(merge_blocks_per_token * a.q_len), dim3(256), 0, stream, args);
+        return hipGetLastError();
+    }
     const void* kernel = a.q_len >= 2 ? attn_kernel<2>(kv_dtype, a.block_table != nullptr) : attn_kernel<1>(kv_dtype, a.block_table != nullptr);
     const int n_here = a.q_len == 1 ? 1 : 2;
-    // Query tokens are worked off in pairs (q0, q0 + 1), one pass over the cache each; an odd count ends
+    // Otherwise query tokens are worked off in pairs (q0, q0 + 1), one pass over the cache each; an odd count ends
     // with the pair (q_len - 2, q_len - 1), which computes token q_len - 2 a second time with the same result.
     // The passes share the partial-result workspace: they are ordered by the stream.
     for (int q0 = 0; q0 < a.q_len; q0 += 2) {
         AttnArgs args = a;
         args.q0 = q0 + n_here <= a.q_len ? q0 : a.q_len - n_here;
+        args.n_here = n_here;
         void* params[] = {&args};
         hipError_t e = hipExtLaunchKernel(kernel, grid, block, params, lds_bytes, stream, q0 == 0 ? ev_before : nullptr,
                                           q0 == 0 ? ev_after : nullptr, 0);
@@ -580,8 +745,7 @@ hipError_t launch_decode_attn(const AttnArgs& a, mfa_kv_dtype kv_dtype, hipStrea
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         if (a.n_wgs > 0 || a.n_splits > 1) {
-            const unsigned blocks = (unsigned)(((size_t)a.B * n_here * kHeads * (kHeadDim / 4) + 255) / 256);
-            hipLaunchKernelGGL(merge_splits_kernel, dim3(blocks), dim3(256), 0, stream, args);
+            hipLaunchKernelGGL(merge_splits_kernel, dim3(merge_blocks_per_token * n_here), dim3(256), 0, stream, args);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
         }

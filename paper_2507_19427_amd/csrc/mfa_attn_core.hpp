@@ -367,6 +367,119 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& 
     pv_unit<BITS != 16>(st, lds_base, vbase, pf, n, g);
 }
 
+// ---- One 32-token unit for NT query tokens held by one wave (the one-pass kernel for three and four query
+// tokens): every key fragment read from LDS feeds NT score products and every value fragment NT weighted-sum
+// products, so the LDS traffic is that of a single token; the NT accumulator chains are independent, which
+// keeps the MFMA pipe busy from one wave.
+//
+// Registers.  NT x 64 accumulator registers and NT x 32 of query fragments leave a wave (the only one on its
+// SIMD) about 130 of its 512 registers for everything else, and only if the accumulators sit in the accumulation
+// half of the file (where just MFMAs reach them) and nothing else does:
+//   * the score products are written out as instructions with ordinary destination registers (the compiler gives
+//     every MFMA of such a kernel an accumulation-register destination, which for NT = 4 alone oversubscribes
+//     that half); the wait states between the last of them and the first read of a score are inserted by hand;
+//   * the accumulators are never rescaled: the reference exponent of a head is set by its first unit with a token
+//     (or handed in) and then stays, and the weights of later tokens may grow to 2^kFixedReferenceLag relative to
+//     it, harmless in bf16 and fp32.  A unit that would exceed that changes nothing and reports the exponents it
+//     would need; the caller starts the segment again with them (decode_bf16_multi_kernel).
+constexpr float kFixedReferenceLag = 40.0f;
+__device__ __forceinline__ void mfma_bf16_into_vgprs(f32x4& acc, const bf16x8& a, const bf16x8& b)
+{
+    asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+template <int NT>
+__device__ __forceinline__ bool process_unit_multi(WaveState (&st)[NT], const QFrags<16> (&q)[NT], lds_ptr_t lds_base, int kbase,
+                                                   int vbase, int unit_t0, const int (&t1)[NT], float scale_log2e, int n, int g,
+                                                   float (&m_wanted)[NT])
+{
+    f32x4 s[NT][2];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) s[t][0] = s[t][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const int k_lane_off = n * 512;
+    auto read_k = [&](int i) {                          // i = 2 * ks + tb
+        return *LDS_AT(bf16x8, lds_base, kbase + (i & 1) * 8192 + k_lane_off + (((4 * (i >> 1) + g) ^ n) << 4));
+    };
+    bf16x8 kf[2] = {read_k(0), read_k(1)};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {                      // key fragments two ahead of their products
+        const bf16x8 k_now = kf[i & 1];
+        if (i + 2 < 16) kf[i & 1] = read_k(i + 2);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) mfma_bf16_into_vgprs(s[t][i & 1], k_now, q[t].f[i >> 1]);
+    }
+    // 16 wait states between an 8-pass MFMA and a read of its result by another unit of the SIMD; every score
+    // passes through this statement, so nothing reads one before it
+    if constexpr (NT == 4)
+        asm volatile("s_nop 7\n\ts_nop 7" : "+v"(s[0][0]), "+v"(s[0][1]), "+v"(s[1][0]), "+v"(s[1][1]), "+v"(s[2][0]), "+v"(s[2][1]),
+                     "+v"(s[3][0]), "+v"(s[3][1]));
+    else
+        asm volatile("s_nop 7\n\ts_nop 7" : "+v"(s[0][0]), "+v"(s[0][1]), "+v"(s[1][0]), "+v"(s[1][1]), "+v"(s[2][0]), "+v"(s[2][1]));
+
+    // (the scores are masked in place, and only in a unit that reaches past a token's end: no second copy of them)
+    float m_ref[NT];
+    bool moved = false;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        if (unit_t0 + kUnitTokens > t1[t]) {           // (a real branch: the empty statement keeps it from becoming 8 selects per unit)
+            asm volatile("");
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int tok = unit_t0 + 16 * (j >> 2) + 4 * g + (j & 3);
+                if (tok >= t1[t]) s[t][j >> 2][j & 3] = -INFINITY;
+            }
+        }
+        float m_raw = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m_raw = fmaxf(m_raw, s[t][j >> 2][j & 3]);
+        const float m_seen = head_max(fmaxf(st[t].m, m_raw * scale_log2e));
+        m_ref[t] = st[t].m == -INFINITY ? m_seen : st[t].m;       // set once, by the head's first unit with a token
+        m_wanted[t] = m_seen;
+        moved = moved || m_seen > m_ref[t] + kFixedReferenceLag;
+    }
+    if (__any(moved)) return false;
+    bf16x8 pf[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const float m_safe = m_ref[t] == -INFINITY ? 0.f : m_ref[t];
+        st[t].m = m_ref[t];
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; j += 2) {
+            // normalise by the sum of the rounded weights actually multiplied into V
+            const float p0 = fast_exp2(__builtin_fmaf(s[t][j >> 2][j & 3], scale_log2e, -m_safe));
+            const float p1 = fast_exp2(__builtin_fmaf(s[t][j >> 2][(j & 3) + 1], scale_log2e, -m_safe));
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            const bf16x2 pb = {(__bf16)p0, (__bf16)p1};
+            pf[t][j] = pb[0];
+            pf[t][j + 1] = pb[1];
+            const uint32_t bits = __builtin_bit_cast(uint32_t, pb);
+            psum += __uint_as_float(bits << 16) + __uint_as_float(bits & 0xFFFF0000u);
+        }
+        st[t].l += psum;
+    }
+    const int v_row = 4 * g + (n >> 2);
+    const int v_lane_off = v_row * 512 + ((n & 3) << 3);
+    union VFrag { bf16x8 v; s16x4 h[2]; };
+    auto read_v = [&](VFrag& f, int db) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+            f.h[tb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, vbase + tb * 8192 + v_lane_off + ((db ^ v_row) << 5)));
+    };
+    constexpr int kAhead = 3;
+    VFrag f[kAhead];
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) read_v(f[i], i);
+#pragma unroll
+    for (int db = 0; db < 16; ++db) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) st[t].acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[db % kAhead].v, pf[t], st[t].acc[db], 0, 0, 0);
+        if (db + kAhead < 16) read_v(f[db % kAhead], db + kAhead);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    return true;
+}
+
 // After the last tile the two waves that share 16 heads (grp 0 and 1: the two token halves of
 // every tile) exchange halves of their accumulators through 64 KB of LDS at xbase (a tile buffer
 // that is dead by then; the caller guarantees that no direct load into it is in flight) and a
@@ -440,9 +553,9 @@ __device__ __forceinline__ void finish_segment(WaveState& st, lds_ptr_t lds_base
     else          finish_half<8, 0>(st, lds_base, xbase, a, r.b, r.slot, r.final_result, wq, grp, lane);
 }
 
-// Two query tokens per sequence (the wave layout is then 2 query tokens x 4 head groups, and every wave
-// has seen all tokens of the segment): no exchange, each wave stores its 16 rows.  The partial of a
-// (segment, query token) sits at slot*2 + query token in the same lane-order layout.  A query token
+// Several query tokens per sequence (a wave then holds all 256 output dims of its 16 heads for a query
+// token, and has seen all tokens of the segment): no exchange, each wave stores its 16 rows.  The partial
+// of a (segment, query token) sits at slot * n_here + query token in the same lane-order layout.  A query token
 // that saw no cached token in this segment leaves m = -inf, l = 0 and a zero accumulator; as a final
 // result that is the zero row.
 __device__ __forceinline__ void finish_segment_two(WaveState& st, const AttnArgs& a, const Segment& r, int qtok, int wq, int lane)
@@ -457,7 +570,7 @@ __device__ __forceinline__ void finish_segment_two(WaveState& st, const AttnArgs
 #pragma unroll
         for (int db = 0; db < 16; ++db) *(f32x4*)(o + 16 * db) = st.acc[db] * inv;
     } else {
-        const size_t slot = (size_t)r.slot * 2 + qtok;
+        const size_t slot = (size_t)r.slot * a.n_here + qtok;
         f32x4* part = (f32x4*)a.ws_acc + slot * (kHeads * kHeadDim / 4) + (size_t)wq * 16 * 64 + lane;
 #pragma unroll
         for (int db = 0; db < 16; ++db) part[db * 64] = st.acc[db];

@@ -55,8 +55,9 @@ struct AttnArgs {
     int32_t n_pages;               // paged only: page ids are clamped into [0, n_pages) when read, rows with ids outside are not written
     int32_t B;
     int32_t q_len;                 // query tokens per sequence (q and out are [B, q_len, 64, 256])
-    int32_t q0;                    // first query token this launch works on: a launch takes token q0 (q_len == 1)
-                                   // or the pair q0, q0 + 1; partial slots of a pair are [.., 2, ..]
+    int32_t q0;                    // first query token this launch works on: a launch takes tokens q0 .. q0 + n_here - 1
+    int32_t n_here;                // query tokens of this launch (1, 2, or 3 / 4 in the one-pass kernel); the partial of
+                                   // (slot, token j of the launch) sits at slot * n_here + j
     int32_t n_wgs;                 // > 0: balanced schedule over this many workgroups; 0: fixed splits below
     int32_t n_splits;
     int32_t chunk_tokens;

@@ -133,8 +133,9 @@ def test_one_token_through_the_multi_entry_point_is_the_single_token_path():
 
 @pytest.mark.parametrize("q_len", [3, 4])
 @pytest.mark.parametrize("kv_dtype,tol", [("bf16", U.TOL_BF16), ("fp8", U.TOL_FP8)])
-def test_three_and_four_tokens_in_pairs(q_len, kv_dtype, tol):
-    """More than two query tokens are worked off pair by pair; an odd count ends with an overlapping pair."""
+def test_three_and_four_tokens(q_len, kv_dtype, tol):
+    """Three and four query tokens: one pass over a bf16 cache (the kernel that keeps all query tokens of a sequence
+    in one wave); pair by pair over the 8-bit cache, an odd count ending with an overlapping pair."""
     _announce(f"{q_len} query tokens, {kv_dtype}")
     lens = [0, 1, 2, 3, 4, 64, 65, 66, 67, 129, 1500, 700]
     case = W.make_contiguous_case("mtp34", 780 + q_len, B=len(lens), S=1504, seq_lens=lens, kv_dtype=kv_dtype, poison=True)
@@ -151,6 +152,67 @@ def test_four_tokens_paged_bitwise_equal_to_contiguous():
     ctx = U.get_ctx()
     got_p, qm = _check(case, ctx, U.TOL_BF16, hint=400, q_len=4)
     assert np.array_equal(got_p, _run_gpu(ctx, contig, qm, hint=400))
+
+
+@pytest.mark.parametrize("q_len", [3, 4])
+def test_one_pass_kernel_restarts_a_segment_whose_scores_outrun_the_reference(q_len):
+    """The one-pass kernel fixes a head's reference exponent at its first unit and starts the segment again with
+    a higher one when a later score exceeds it by more than 2^40.  Planted: keys aligned with the queries of some
+    heads, far into the sequence and in different tiles, whose scores lie 60 to 140 (natural units) above the
+    rest -- for a few heads of one head group only, for all heads, twice in a row (a second, larger outlier after
+    the first), and in the last tile.  The result must be the usual softmax: practically the outlier's value row."""
+    _announce(f"{q_len} query tokens, outlier scores force restarts")
+    lens = [700, 300, 130, 2000]
+    case = W.make_contiguous_case("mtprestart", 795 + q_len, B=len(lens), S=2000, seq_lens=lens, poison=True)
+    qm = W.make_multi_query(case, q_len, 796)
+    k = case.k.float()
+    qf = qm.float()
+
+    def plant(b, pos, heads, tok, gain):
+        # key row pos of sequence b := gain * (mean of the chosen heads' queries of query token tok), so that
+        # those heads score about gain * |q|^2 / 16 on it
+        qv = qf[b, tok, heads].mean(0)
+        k[b, pos] = gain * qv / qv.norm() ** 2 * 16.0 * len(heads) ** 0.0
+
+    plant(0, 333, [3, 4, 5], 0, 60.0)                    # one head group only: the other waves must restart with it
+    plant(1, 77, list(range(64)), q_len - 1, 30.0)       # weak for most heads (mean over 64 queries): may or may not trip
+    plant(2, 70, [17], 1, 80.0)
+    plant(2, 127, [17], 1, 140.0)                        # a second, larger outlier later in the same sequence
+    plant(3, 1990, [60, 61, 62, 63], 0, 100.0)           # in the last tile of a long sequence cut over workgroups
+    case.k = k.to(torch.bfloat16)
+    got = _run_gpu(U.get_ctx(), case, qm)
+    ref = _oracle(case, qm)
+    err = U.row_normalised_error(got, ref)
+    print(f"   row-normalised max error {err:.3e}", flush=True)
+    assert err <= U.TOL_BF16
+    # the planted key dominates its head: the output is that token's value row
+    assert np.abs(got[0, 0, 4] - case.v[0, 333].float().numpy()).max() <= 1e-2 * np.abs(case.v[0, 333].float().numpy()).max()
+    assert np.array_equal(got, _run_gpu(U.get_ctx(), case, qm))           # and bitwise reproducible
+
+
+@pytest.mark.parametrize("q_len", [3, 4])
+def test_three_and_four_tokens_at_benchmark_size_on_sampled_rows(q_len):
+    """B = 64, context 4096 (the benchmark's cache), one pass for three and for four query tokens."""
+    _announce(f"{q_len} query tokens at B=64 ctx=4096")
+    ctx = U.get_ctx()
+    case = W.config2_step3(poison=False)
+    qm = W.make_multi_query(case, q_len, 797)
+    got = _run_gpu(ctx, case, qm)
+    assert np.isfinite(got).all()
+    rows = U.sample_rows(case, 24)
+    ref = _oracle(case, qm, rows=rows)                                  # [rows, q_len, D] stacked on axis 1
+    sub = np.stack([got[b, :, h] for b, h in rows])
+    err = U.row_normalised_error(sub, ref)
+    print(f"   sampled rows {len(rows)} x {q_len} tokens: row-normalised max error {err:.3e}", flush=True)
+    assert err <= U.TOL_BF16
+
+
+def test_four_tokens_beyond_the_one_pass_kernels_batch_limit_fall_back_to_pairs():
+    _announce("4 query tokens, B=600 (pairs)")
+    g = torch.Generator().manual_seed(798)
+    lens = torch.randint(0, 90, (600,), generator=g).tolist()
+    case = W.make_contiguous_case("mtp600", 799, B=600, S=96, seq_lens=lens, poison=True)
+    _check(case, U.get_ctx(max_batch=1024, max_seq_len=4096), U.TOL_BF16, q_len=4)
 
 
 def test_unsupported_query_counts_are_refused():
