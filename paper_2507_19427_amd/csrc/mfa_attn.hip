@@ -29,6 +29,8 @@
 namespace mfa {
 
 constexpr int kSlotBytes = 2 * kUnitBytes;            // one 64-token tile: two unit images
+constexpr int kLoadsPerTileAndWave = 8;               // direct loads a wave of decode_bf16_kernel issues per tile (4 rows pairs x K, V)
+static_assert(kLoadsPerTileAndWave == 8, "schedule_begin waits with s_waitcnt vmcnt(8) for the loads older than a tile's");
 constexpr int kAttnLdsBytes = 2 * kSlotBytes;         // bf16 kernel: 128 KB
 
 
@@ -72,7 +74,9 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     // Wave w brings rows [8w, 8w+8) of a tile's K and V: all in unit w/4.  Rows at or past the segment's
     // end re-read its last valid token, so nothing outside the sequence is touched and every LDS row
     // holds finite data (the weights of those rows are masked to zero).
-    auto issue_tile = [&](const Segment& sg, int tile, int slot, int page) {
+    // (guessed: the tile named by guess_first_tile, whose position comes out of vector arithmetic; its
+    // addresses stay in vector registers)
+    auto issue_tile = [&](const Segment& sg, int tile, int slot, int page, bool guessed = false) {
         const int tile_t0 = sg.t0 + tile * kTile;
         const int64_t row0 = tile_row0<PAGED>(a, sg.b, tile_t0, page);
         const unsigned char* k_tile = (const unsigned char*)a.k + row0 * 512;   // wave-uniform: scalar registers
@@ -88,8 +92,13 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
             const int cv = ((((p16 >> 1) ^ key) << 1) | (p16 & 1));
             const int first_row = 8 * wave + 2 * u;                   // wave-uniform
             const uint32_t dst = lds_addr0 + slot * kSlotBytes + (first_row >> 5) * kUnitBytes + (first_row & 31) * 512;
-            load_to_lds_16B(k_tile, (uint32_t)(in_tile * 512 + ck * 16), dst);
-            load_to_lds_16B(v_tile, (uint32_t)(in_tile * 512 + cv * 16), dst + kUnitVOffset);
+            if (guessed) {
+                load_to_lds_16B_vaddr(k_tile + (uint32_t)(in_tile * 512 + ck * 16), dst);
+                load_to_lds_16B_vaddr(v_tile + (uint32_t)(in_tile * 512 + cv * 16), dst + kUnitVOffset);
+            } else {
+                load_to_lds_16B(k_tile, (uint32_t)(in_tile * 512 + ck * 16), dst);
+                load_to_lds_16B(v_tile, (uint32_t)(in_tile * 512 + cv * 16), dst + kUnitVOffset);
+            }
         }
     };
     auto load_q = [&](QFrags<16>& q, const Segment& sg) {
@@ -99,13 +108,33 @@ __global__ __launch_bounds__(kAttnThreads) void decode_bf16_kernel(AttnArgs a)
     // The workgroup's segments are worked off as one stream of tiles: while the last tile of a segment is
     // multiplied, the first tile of the next one is already on its way into the other slot,
     // and the end-of-segment exchange uses the slot of the tile just finished.
-    Schedule sched = schedule_begin(a, lds_base);
+    //
+    // The very first tile is asked for before the schedule is known: the lengths are requested first
+    // (stage_lengths), then the tile that would be this workgroup's first if every sequence had the length of
+    // the hint -- its place follows from the launch arguments alone -- and the schedule is worked out while
+    // those 64 KB are on their way (the lengths, requested earlier, arrive earlier).  When the schedule
+    // disagrees (ragged lengths), the right tile goes into the other slot and the guessed one is never looked
+    // at; the guess only ever names whole tiles below the hint, i.e. memory the caller has vouched for.
+    stage_lengths(a, lds_base);
+    const FirstTileGuess guess = guess_first_tile(a);
+    if (guess.valid) {
+        Segment gs;
+        gs.b = guess.b; gs.t0 = guess.t0; gs.t1 = guess.t0 + kTile;
+        issue_tile(gs, 0, 0, lookup_page<PAGED>(a, guess.b, guess.t0), true);   // kLoadsPerTileAndWave loads
+    }
+    Schedule sched = schedule_begin(a, lds_base, guess.valid ? kLoadsPerTileAndWave : 0);
     Segment r, r_next;
-    if (!schedule_next(a, lds_base, sched, r)) return;
+    if (!schedule_next(a, lds_base, sched, r)) {
+        wait_vmem_all();                              // nothing may still be writing into this workgroup's LDS when it ends
+        return;
+    }
     QFrags<16> q;
     load_q(q, r);
     int slot0 = 0;                                    // slot of the segment's first tile
-    issue_tile(r, 0, 0, lookup_page<PAGED>(a, r.b, r.t0));
+    if (!(guess.valid && r.b == guess.b && r.t0 == guess.t0 && r.t0 + kTile <= r.t1)) {
+        slot0 = guess.valid ? 1 : 0;
+        issue_tile(r, 0, slot0, lookup_page<PAGED>(a, r.b, r.t0));
+    }
     for (bool more = true; more;) {
         const int end_mine = r.len - (a.q_len - 1 - a.q0 - grp);      // QL == 2: grp = query token of the pair
         const int t1_mine = QL == 2 ? (r.t1 < end_mine ? r.t1 : end_mine) : r.t1;
@@ -203,6 +232,7 @@ __global__ __launch_bounds__(kMultiThreads) void decode_bf16_multi_kernel(AttnAr
     // A word of LDS behind the schedule's tables: set by a wave whose unit was refused (a score more than
     // 2^kFixedReferenceLag above its head's reference exponent), seen by all waves after the next barrier.
     constexpr int kRestartFlag = kAttnLdsTotal - 4;
+    stage_lengths(a, lds_base);
     Schedule sched = schedule_begin(a, lds_base);
     Segment r;
     bool first_segment = true;
@@ -363,6 +393,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
     const int n = lane & 15;
     const int g = lane >> 4;
 
+    stage_lengths(a, lds_base);
     Schedule sched = schedule_begin(a, lds_base);
     Segment r;
     bool first_segment = true;

@@ -54,6 +54,19 @@ __device__ __forceinline__ void load_to_lds_16B(const void* sbase, uint32_t voff
                  :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
 }
 
+// The same with the whole address in a pair of vector registers (for a base the compiler keeps there).
+__device__ __forceinline__ void load_to_lds_16B_vaddr(const void* vaddr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
+                 :: "v"(vaddr), "s"(lds_addr) : "memory");
+}
+// Four bytes per lane: lane l's word lands at lds_addr + 4*l.
+__device__ __forceinline__ void load_to_lds_4B(const void* sbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+
 // max over the four lanes {n, n+16, n+32, n+48} that hold one head, without touching LDS:
 // v_permlane32_swap exchanges the upper half of the first operand with the lower half of the
 // second, v_permlane16_swap exchanges odd 16-lane rows of the first with even rows of the second.
@@ -670,7 +683,30 @@ __device__ __forceinline__ int range_index()
 // also leaves the tables in LDS for the later segments, which are requested only after the
 // barriers of the first one.  Larger batches: one cooperative scan through LDS.
 constexpr int kWaveScanChunks = 8;
-__device__ __forceinline__ Schedule schedule_begin(const AttnArgs& a, lds_ptr_t lds_base)
+// The lengths of such a batch reach the waves through LDS: every wave copies seq_lens[0 .. B) there with direct
+// loads (all waves write the same bytes to the same place, so a wave that has waited for its own loads has the
+// lengths without a barrier).  Direct loads are counted like every vector-memory operation but wait for nothing
+// themselves, so a kernel can ask for the lengths, then for its first tile, and work the schedule out as soon as
+// the lengths -- the older loads -- are there: stage_lengths(), further loads, schedule_begin(.., loads issued
+// since).  The staging area is the part of the prefix-sum table that only larger batches use.
+constexpr int kSchedStagedLensOffset = kSchedLdsOffset + 8192;
+static_assert(kSchedStagedLensOffset >= kSchedLdsOffset + (kWaveScanChunks * 64 + 1) * 4 &&
+              kSchedStagedLensOffset + kWaveScanChunks * 256 <= kSchedTotalsOffset, "staged lengths lie in the unused part of the table");
+__device__ __forceinline__ bool lengths_are_staged(const AttnArgs& a) { return a.n_wgs != 0 && a.B <= kWaveScanChunks * 64; }
+__device__ __forceinline__ void stage_lengths(const AttnArgs& a, lds_ptr_t lds_base)
+{
+    if (!lengths_are_staged(a)) return;
+    const int lane = threadIdx.x & 63;
+    const uint32_t dst = (uint32_t)(uintptr_t)lds_base + kSchedStagedLensOffset;
+#pragma unroll
+    for (int c = 0; c < kWaveScanChunks; ++c)
+        if (c * 64 < a.B) {
+            const int i = c * 64 + lane < a.B ? c * 64 + lane : a.B - 1;      // lanes past the batch repeat its last entry
+            load_to_lds_4B(a.seq_lens, (uint32_t)i * 4u, dst + c * 256);
+        }
+}
+// later_loads: vector-memory operations this wave has issued since stage_lengths (0 or 8: a tile)
+__device__ __forceinline__ Schedule schedule_begin(const AttnArgs& a, lds_ptr_t lds_base, int later_loads = 0)
 {
     Schedule s;
     s.first_known = false;
@@ -680,11 +716,16 @@ __device__ __forceinline__ Schedule schedule_begin(const AttnArgs& a, lds_ptr_t 
     const int wave = threadIdx.x >> 6;
 
     if (a.B <= kWaveScanChunks * 64) {
+        // the staged lengths have landed once only the loads issued after them are outstanding
+        if (later_loads == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else                  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         int len[kWaveScanChunks], p1[kWaveScanChunks];
 #pragma unroll
         for (int c = 0; c < kWaveScanChunks; ++c) {
             const int i = c * 64 + lane;
-            len[c] = (c * 64 < a.B && i < a.B) ? clamped_len(a, i) : 0;
+            int L = 0;
+            if (c * 64 < a.B && i < a.B) L = *LDS_AT(int, lds_base, kSchedStagedLensOffset + i * 4);
+            len[c] = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
         }
         int N = 0;
 #pragma unroll
@@ -771,6 +812,32 @@ __device__ __forceinline__ Schedule schedule_begin(const AttnArgs& a, lds_ptr_t 
     __syncthreads();
     s.b = __builtin_amdgcn_readfirstlane(*LDS_AT(int, lds_base, found));   // the one sequence with P[b] <= lo < P[b + 1]
     return s;
+}
+
+// Where this workgroup's first tile lies if every sequence has the length of the hint: computed from the
+// launch arguments alone (no device memory is read), with the same arithmetic as the schedule.  Only whole
+// tiles below the hint are named, so that a load of the guessed tile stays inside memory the caller has
+// vouched for (rows below max_seq_len_hint of a sequence below B; paged: a table entry below
+// ceil(hint / 64), clamped into the pool like every other).
+struct FirstTileGuess { int b, t0; bool valid; };
+__device__ __forceinline__ FirstTileGuess guess_first_tile(const AttnArgs& a)
+{
+    FirstTileGuess gs;
+    gs.b = gs.t0 = 0;
+    gs.valid = false;
+    if (!lengths_are_staged(a)) return gs;            // (the guess rides on the staged lengths' head start)
+    const int T = (a.max_seq_len_hint + kTile - 1) / kTile;
+    const int N = a.B * T;
+    const int G = a.n_wgs < N ? a.n_wgs : N;
+    const int w = range_index();
+    if (w >= G) return gs;
+    const int lo = scaled_floor(w, N, G);
+    gs.b = (int)div_floor_u32((unsigned)lo, (unsigned)T);
+    gs.t0 = (lo - gs.b * T) * kTile;
+    gs.b = __builtin_amdgcn_readfirstlane(gs.b);
+    gs.t0 = __builtin_amdgcn_readfirstlane(gs.t0);
+    gs.valid = gs.b < a.B && gs.t0 + kTile <= a.max_seq_len_hint;
+    return gs;
 }
 
 // The next segment of this workgroup, or false when it has none left.  A false return for the very
