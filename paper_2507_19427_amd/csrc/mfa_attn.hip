@@ -468,9 +468,10 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                         half[w >> 1][4 * (w & 1) + 2] = p23[0];
                         half[w >> 1][4 * (w & 1) + 3] = p23[1];
                     }
-                    const int off = image * kLbVImageBytes + i * kPaddedVUnitBytes + prow * kPaddedVRow + (pchunk << 5);
+                    // (halves swapped in the upper half of a row: see pv_unit)
+                    const int off = image * kLbVImageBytes + i * kPaddedVUnitBytes + prow * kPaddedVRow + (pchunk << 5) + ((pchunk & 8) << 1);
                     *LDS_AT(bf16x8, lds_base, off) = half[0];
-                    *LDS_AT(bf16x8, lds_base, off + 16) = half[1];
+                    *LDS_AT(bf16x8, lds_base, off ^ 16) = half[1];
                 }
             } else {
                 // 32 elements = bf16 chunks 2*pchunk and 2*pchunk + 1 (32 bytes each) of row prow
@@ -483,8 +484,8 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                     const bf16x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 2);
                     const bf16x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 3);
                     const bf16x8 eight = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
-                    const int chunk = 2 * pchunk + (w >> 1);
-                    *LDS_AT(bf16x8, lds_base, row_off + (chunk << 5) + (w & 1) * 16) = eight;
+                    // piece w of this thread's 64-byte group; rotated by one in the upper half of a row (see pv_unit)
+                    *LDS_AT(bf16x8, lds_base, row_off + (pchunk << 6) + (((w + (pchunk >> 2)) & 3) << 4)) = eight;
                 }
             }
             if (threadIdx.x < 128) *LDS_AT(float, lds_base, kLbScaleBase + image * 512 + threadIdx.x * 4) = t.scale;
@@ -531,7 +532,7 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
             {
                 const bf16x8 pf = softmax_unit<BITS>(st, q, raw0, lds_base, r.t0 + t * kTile + u0 * kUnitTokens, t1_mine,
                                                      a.scale_log2e, g, scales + u0 * kUnitTokens * 4, scales + 256 + u0 * kUnitTokens * 4);
-                pv_unit<true>(st, lds_base, vb + u0 * kPaddedVUnitBytes, pf, n, g);
+                pv_unit<BITS>(st, lds_base, vb + u0 * kPaddedVUnitBytes, pf, n, g);
             }
             if (QL == 2)
                 process_unit<BITS>(st, q, lds_base, kb + kUnitTokens * kRowBytes, vb + kPaddedVUnitBytes,

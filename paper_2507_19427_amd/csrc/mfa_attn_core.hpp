@@ -335,23 +335,38 @@ __device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& 
 }
 
 // Second half of a unit: O^T += V^T P^T over the unit's 32 tokens.
-//   PADDED = false (bf16 cache, rows written by direct loads): 512-byte rows, 32-byte chunk c of row r at c ^ (r & 15).
-//   PADDED = true  (8 / 4 bit caches, rows written from registers): rows kPaddedVRow = 544 bytes apart and in plain
-//                  order.  The 32 bytes of padding shift consecutive rows by eight banks, which spreads a transposing
-//                  read (4 rows x 32 bytes per 16 lanes, 8 rows per half wave) over all 64 banks as the XOR does,
-//                  and every operand address is then one lane register plus a compile-time offset.
+//   BITS = 16 (bf16 cache, rows written by direct loads): 512-byte rows, 32-byte chunk c of row r at c ^ (r & 15).
+//   BITS = 8 / 4 (rows written from registers): rows kPaddedVRow = 544 bytes apart.  The 32 bytes of padding shift
+//                  consecutive rows by eight banks, which spreads a transposing read (4 rows x 32 bytes per 16 lanes,
+//                  8 rows per half wave) over all 64 banks as the XOR does, and every operand address is then one
+//                  lane register plus a compile-time offset.  Within a row the 16-byte pieces are placed so that the
+//                  16 lanes of one store instruction hit 16 different bank groups (store_tile in
+//                  decode_lowbit_kernel); in the plain order they collide two by two:
+//                    8 bit: a thread owns one 32-byte chunk; in the upper half of a row (chunks 8..15) its two
+//                           16-byte halves are swapped;
+//                    4 bit: a thread owns a 64-byte group of four pieces; in the upper half of a row (groups 4..7)
+//                           piece w sits at position (w + 1) & 3 of its group.
+//                  A reader knows the chunk (db) at compile time, so undoing this costs it two more lane registers
+//                  and no instruction.
 constexpr int kPaddedVRow = 544;
 constexpr int kPaddedVUnitBytes = kUnitTokens * kPaddedVRow;      // 17408
-template <bool PADDED>
+template <int BITS>
 __device__ __forceinline__ void pv_unit(WaveState& st, lds_ptr_t lds_base, int vbase, const bf16x8& pf, int n, int g)
 {
+    constexpr bool PADDED = BITS != 16;
     const int v_row = 4 * g + (n >> 2);                 // V: row within a 16-token block (= swizzle key)
-    const int v_lane_off = v_row * (PADDED ? kPaddedVRow : 512) + ((n & 3) << 3);
+    const int piece = n & 3;                            // which 8 bytes of the 32-byte chunk this lane supplies
+    const int v_lane_off = v_row * (PADDED ? kPaddedVRow : 512) + (piece << 3);
+    // upper half of a padded row, even / odd chunk (relative to the chunk's plain place db << 5)
+    const int v_lane_off_upper_even = BITS == 8 ? v_lane_off ^ 16 : v_lane_off + 16;
+    const int v_lane_off_upper_odd = BITS == 8 ? v_lane_off ^ 16
+                                               : v_row * kPaddedVRow + (piece < 2 ? 16 + 8 * piece : 8 * piece - 48);
     union VFrag { bf16x8 v; s16x4 h[2]; };
     auto read_v = [&](VFrag& f, int db) {
+        const int lane_off = !PADDED || db < 8 ? v_lane_off : ((db & 1) ? v_lane_off_upper_odd : v_lane_off_upper_even);
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
-            const int off = PADDED ? vbase + tb * 16 * kPaddedVRow + v_lane_off + (db << 5)
+            const int off = PADDED ? vbase + tb * 16 * kPaddedVRow + lane_off + (db << 5)
                                    : vbase + tb * 8192 + v_lane_off + ((db ^ v_row) << 5);
             f.h[tb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
         }
@@ -377,7 +392,7 @@ __device__ __forceinline__ void process_unit(WaveState& st, const QFrags<BITS>& 
                                              int kscale_off, int vscale_off)
 {
     const bf16x8 pf = score_unit<BITS>(st, q, lds_base, kbase, unit_t0, t1, scale_log2e, n, g, kscale_off, vscale_off);
-    pv_unit<BITS != 16>(st, lds_base, vbase, pf, n, g);
+    pv_unit<BITS>(st, lds_base, vbase, pf, n, g);
 }
 
 // ---- One 32-token unit for NT query tokens held by one wave (the one-pass kernel for three and four query
