@@ -468,8 +468,8 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                         half[w >> 1][4 * (w & 1) + 2] = p23[0];
                         half[w >> 1][4 * (w & 1) + 3] = p23[1];
                     }
-                    // (halves swapped in the upper half of a row: see pv_unit)
-                    const int off = image * kLbVImageBytes + i * kPaddedVUnitBytes + prow * kPaddedVRow + (pchunk << 5) + ((pchunk & 8) << 1);
+                    // (halves swapped in some chunks: see pv_unit)
+                    const int off = image * kLbVImageBytes + i * kPaddedVUnitBytes + prow * kPaddedVRow + (pchunk << 5) + (padded_v_halves_swapped(pchunk) ? 16 : 0);
                     *LDS_AT(bf16x8, lds_base, off) = half[0];
                     *LDS_AT(bf16x8, lds_base, off ^ 16) = half[1];
                 }
@@ -484,8 +484,8 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
                     const bf16x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 2);
                     const bf16x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(t.piece[0][w], 1.0f, 3);
                     const bf16x8 eight = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
-                    // piece w of this thread's 64-byte group; rotated by one in the upper half of a row (see pv_unit)
-                    *LDS_AT(bf16x8, lds_base, row_off + (pchunk << 6) + (((w + (pchunk >> 2)) & 3) << 4)) = eight;
+                    // piece w of this thread's 64-byte group, rotated within the group (see pv_unit)
+                    *LDS_AT(bf16x8, lds_base, row_off + (pchunk << 6) + (((w + padded_v_rotation(pchunk)) & 3) << 4)) = eight;
                 }
             }
             if (threadIdx.x < 128) *LDS_AT(float, lds_base, kLbScaleBase + image * 512 + threadIdx.x * 4) = t.scale;

@@ -340,16 +340,18 @@ __device__ __forceinline__ bf16x8 score_unit(WaveState& st, const QFrags<BITS>& 
 //                  consecutive rows by eight banks, which spreads a transposing read (4 rows x 32 bytes per 16 lanes,
 //                  8 rows per half wave) over all 64 banks as the XOR does, and every operand address is then one
 //                  lane register plus a compile-time offset.  Within a row the 16-byte pieces are placed so that the
-//                  16 lanes of one store instruction hit 16 different bank groups (store_tile in
-//                  decode_lowbit_kernel); in the plain order they collide two by two:
-//                    8 bit: a thread owns one 32-byte chunk; in the upper half of a row (chunks 8..15) its two
-//                           16-byte halves are swapped;
-//                    4 bit: a thread owns a 64-byte group of four pieces; in the upper half of a row (groups 4..7)
-//                           piece w sits at position (w + 1) & 3 of its group.
-//                  A reader knows the chunk (db) at compile time, so undoing this costs it two more lane registers
-//                  and no instruction.
+//                  lanes of one 16-byte store instruction (store_tile in decode_lowbit_kernel) spread over the banks
+//                  whether the hardware takes them 8 or 16 at a time; in the plain order they collide two by two:
+//                    8 bit: a thread owns the 32-byte chunk c of a row; its two 16-byte halves are swapped when
+//                           bits 2 and 3 of c differ (chunks 4..11);
+//                    4 bit: a thread owns the 64-byte group c of four pieces; piece w sits at position
+//                           (w + (c >> 1)) & 3 of the group.
+//                  A reader knows the chunk (db) at compile time, so undoing this costs it lane registers (one more
+//                  for 8 bit, three for 4 bit) and no instruction.
 constexpr int kPaddedVRow = 544;
 constexpr int kPaddedVUnitBytes = kUnitTokens * kPaddedVRow;      // 17408
+__host__ __device__ constexpr bool padded_v_halves_swapped(int chunk32) { return (((chunk32 >> 2) ^ (chunk32 >> 3)) & 1) != 0; }
+__host__ __device__ constexpr int padded_v_rotation(int group64) { return (group64 >> 1) & 3; }
 template <int BITS>
 __device__ __forceinline__ void pv_unit(WaveState& st, lds_ptr_t lds_base, int vbase, const bf16x8& pf, int n, int g)
 {
@@ -357,16 +359,24 @@ __device__ __forceinline__ void pv_unit(WaveState& st, lds_ptr_t lds_base, int v
     const int v_row = 4 * g + (n >> 2);                 // V: row within a 16-token block (= swizzle key)
     const int piece = n & 3;                            // which 8 bytes of the 32-byte chunk this lane supplies
     const int v_lane_off = v_row * (PADDED ? kPaddedVRow : 512) + (piece << 3);
-    // upper half of a padded row, even / odd chunk (relative to the chunk's plain place db << 5)
-    const int v_lane_off_upper_even = BITS == 8 ? v_lane_off ^ 16 : v_lane_off + 16;
-    const int v_lane_off_upper_odd = BITS == 8 ? v_lane_off ^ 16
-                                               : v_row * kPaddedVRow + (piece < 2 ? 16 + 8 * piece : 8 * piece - 48);
+    // 8 bit: [1] = halves swapped.  4 bit: [k] = the chunk's first piece sits at position k of its 64-byte group
+    // (offsets relative to the group).
+    int v_lane_alt[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        v_lane_alt[k] = BITS == 8 ? (k == 1 ? v_lane_off ^ 16 : v_lane_off)
+                                  : v_row * kPaddedVRow + 16 * ((k + (piece >> 1)) & 3) + 8 * (piece & 1);
     union VFrag { bf16x8 v; s16x4 h[2]; };
     auto read_v = [&](VFrag& f, int db) {
-        const int lane_off = !PADDED || db < 8 ? v_lane_off : ((db & 1) ? v_lane_off_upper_odd : v_lane_off_upper_even);
+        int lane_off = v_lane_off, place = db << 5;
+        if (BITS == 8) lane_off = v_lane_alt[padded_v_halves_swapped(db) ? 1 : 0];
+        if (BITS == 4) {
+            lane_off = v_lane_alt[(2 * (db & 1) + padded_v_rotation(db >> 1)) & 3];
+            place = (db >> 1) << 6;
+        }
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
-            const int off = PADDED ? vbase + tb * 16 * kPaddedVRow + lane_off + (db << 5)
+            const int off = PADDED ? vbase + tb * 16 * kPaddedVRow + lane_off + place
                                    : vbase + tb * 8192 + v_lane_off + ((db ^ v_row) << 5);
             f.h[tb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AT(s16x4, lds_base, off));
         }
