@@ -559,7 +559,17 @@ __global__ __launch_bounds__(kAttnThreads) void decode_lowbit_kernel(AttnArgs a)
 __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
 {
     const int n_here = a.n_here;                                      // query tokens of this launch
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;        // over B * n_here * 4096 float4
+    // 16 blocks per (sequence, query token).  Consecutive block indices go to consecutive dies; the streaming kernel
+    // has numbered its ranges so that a die holds consecutive ranges (range_index), i.e. with lengths that are about
+    // equal the partial results of row r of B * n_here were written on die r * 8 / (B * n_here): the blocks of a
+    // die take the rows of that die.
+    const unsigned rows = (unsigned)(a.B * n_here);
+    unsigned block = blockIdx.x;
+    if ((rows & 7u) == 0 && a.n_wgs > 0 && (a.n_wgs & 7) == 0 && gridDim.x == rows * 16u) {
+        const unsigned die = block & 7u, j = block >> 3;
+        block = (die * (rows >> 3) + (j >> 4)) * 16u + (j & 15u);
+    }
+    const size_t idx = (size_t)block * 256 + threadIdx.x;             // over B * n_here * 4096 float4
     const int p = (int)(idx & 4095);                                  // position in the partial's lane-order layout
     const int bq = (int)(idx >> 12);                                  // sequence * n_here + query token of the launch
     if (bq >= a.B * n_here) return;
@@ -570,7 +580,11 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
     const int wq = p >> 10;
     const int h = 16 * wq + (lane & 15);
     const int d = 16 * db + 4 * (lane >> 4);
+    // (the length and the sequence's slot record are asked for together: one round trip, not two; the record of
+    // a sequence without tokens holds whatever the workspace held and is not used)
     int L = a.seq_lens[b];
+    const int rec_first = a.n_wgs > 0 ? a.ws_seg[2 * b] : 0;
+    const int rec_count = a.n_wgs > 0 ? a.ws_seg[2 * b + 1] : 0;
     L = L < 0 ? 0 : (L > a.max_seq_len_hint ? a.max_seq_len_hint : L);
     float4* const o = (float4*)(a.out + (((size_t)b * a.q_len + a.q0 + qtok) * kHeads + h) * kHeadDim + d);
     const int L_mine = L - (a.q_len - 1 - a.q0 - qtok);               // tokens this query token attends to
@@ -578,8 +592,8 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(AttnArgs a)
     size_t item0;
     if (a.n_wgs > 0) {                                                // balanced schedule
         if (L == 0) { *o = make_float4(0.f, 0.f, 0.f, 0.f); return; }
-        item0 = (size_t)a.ws_seg[2 * b];
-        n_valid = a.ws_seg[2 * b + 1];
+        item0 = (size_t)rec_first;
+        n_valid = rec_count;
         if (n_valid == 1 && n_here < 3) return;                       // one workgroup held it all and wrote the result
                                                                       // (the one-pass kernel for 3 / 4 tokens never does)
     } else {
