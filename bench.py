@@ -37,12 +37,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak
 # WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for a 256 MiB device copy, as
 # recorded in the named file under profiles/ (which gives the command and the library it was taken on).
 PROFILED_TRAFFIC = {
-    "cfg2": (132261 * 2.000 * 1024 + 16512 * 1.000 * 1024, "profiles/decode_attn_cfg2_b64_ctx4096_hbm_traffic.md"),
-    "cfg4": (262565 * 2.000 * 1024 + 16512 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
-    "cfg5": (276242 * 2.000 * 1024 + 16513 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
-    "fp4": (140225 * 2.000 * 1024 + 16513 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
-    "cfg2q2": (133271 * 2.000 * 1024 + 33024 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
-    "cfg2q4": (135338 * 2.000 * 1024 + 66048 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+    "cfg2": (132256 * 2.000 * 1024 + 16512 * 1.000 * 1024, "profiles/decode_attn_cfg2_b64_ctx4096_hbm_traffic.md"),
+    "cfg4": (262560 * 2.000 * 1024 + 16512 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+    "cfg5": (276254 * 2.000 * 1024 + 16513 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+    "fp4": (140121 * 2.000 * 1024 + 16513 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+    "cfg2q2": (133280 * 2.000 * 1024 + 33024 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
+    "cfg2q4": (135336 * 2.000 * 1024 + 66048 * 1024, "profiles/decode_attn_other_workloads_hbm_traffic.md"),
 }
 Q_BYTES_PER_SEQ = 64 * 256 * 2
 OUT_BYTES_PER_SEQ = 64 * 256 * 4
