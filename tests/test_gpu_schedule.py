@@ -87,6 +87,24 @@ def test_paged_ragged_many_sequences_bitwise_equal_to_contiguous():
     assert np.array_equal(got_p, got_c)
 
 
+@pytest.mark.parametrize("lens", [
+    [6000] + [3] * 63,                                   # one sequence holds nearly every tile: its pieces span all dies
+    [1] * 56 + [2500] * 8,                               # all the work in the last eighth of the rows
+    [700, 0, 0, 0, 0, 0, 0, 9000] * 2,                   # 16 rows, two long ones per eight
+    [300 + 37 * i for i in range(64)],                   # steadily growing lengths
+])
+def test_merge_row_placement_is_only_a_matter_of_speed(lens):
+    """The merge kernel hands its workgroups the rows that a batch of equal lengths would have left on their own die.
+    With lengths as unequal as these the guess is wrong for most rows; the result must not depend on it.  Batches whose
+    size is a multiple of 8 with at least 256 tiles, so that the placement is in force."""
+    _announce(f"skewed lengths, B={len(lens)}")
+    case = W.make_contiguous_case("skew", 360 + len(lens), B=len(lens), S=max(lens) + 2, seq_lens=lens, poison=True)
+    got = _check(case, U.get_ctx(), U.TOL_BF16)
+    assert np.array_equal(got, U.run_gpu(U.get_ctx(), case))
+    fixed = U.get_ctx(schedule=mfa.MFA_SCHEDULE_FIXED)  # another schedule, another merge order: same rows within tolerance
+    assert U.row_normalised_error(U.run_gpu(fixed, case), U.run_oracle(case)) <= U.TOL_BF16
+
+
 def test_fp8_more_sequences_than_workgroups():
     _announce("fp8 B=280 short ragged")
     lens = _lens(341, 280, 1, 300, zeros=9)
